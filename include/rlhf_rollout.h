@@ -1,0 +1,240 @@
+/*
+ * rlhf_rollout.h -- C ABI of the MI355X (gfx950) rollout library.
+ *
+ * The library covers the experience-generation step of PPO stage 3 as the
+ * paper frames it (Section 2.1, "RLHF Training"): the actor generates a
+ * response token by token against a key/value cache, and the generated
+ * positions are then scored by the actor and the reference model to obtain
+ * per-token log-probabilities and the penalty on policy deviation.  The cache
+ * lives in ONE preallocated arena cut into fixed pages, which is this
+ * library's answer to the paper's finding that the inference phases of RLHF
+ * leave an allocator full of cached blocks of assorted sizes that later
+ * requests cannot reuse (Section 3.1; Appendix A): nothing is ever taken from
+ * or returned to the driver between create and destroy, so the paper's
+ * fragmentation event (Section 3, first paragraph; Appendix B: reserved minus
+ * allocated at the moment the allocator must call the driver) cannot occur.
+ *
+ * Conventions
+ *   - Every function returns an rlhf_status.  No C++ exception crosses the
+ *     boundary.  rlhf_last_error_string() gives text for the last failure on
+ *     the calling thread.
+ *   - "dev" pointers are device memory owned by the caller (for example a
+ *     torch tensor's data_ptr()); "host" pointers are ordinary host memory and
+ *     are fully read before the call returns.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls that launch work enqueue it on that stream and return without
+ *     synchronising, except where stated.
+ *   - One arena may be used by one host thread at a time.
+ *   - Compute entry points fail with RLHF_ERR_DEVICE when no HIP device is
+ *     usable; there is no CPU fallback.
+ */
+#ifndef RLHF_ROLLOUT_H
+#define RLHF_ROLLOUT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    RLHF_OK = 0,
+    RLHF_ERR_INVALID = -1,     /* NULL pointer, bad shape, id out of range, misaligned buffer */
+    RLHF_ERR_OOM = -2,         /* arena has too few free pages; state unchanged */
+    RLHF_ERR_DEVICE = -3,      /* a HIP call failed */
+    RLHF_ERR_UNSUPPORTED = -4  /* dtype / head_dim / page size outside what the kernels cover */
+} rlhf_status;
+
+typedef enum { RLHF_F16 = 0, RLHF_BF16 = 1, RLHF_F32 = 2 } rlhf_dtype;
+
+/* Tokens per page.  The kernels are written for this value only. */
+#define RLHF_PAGE_TOKENS 16
+
+/* ------------------------------------------------------------------------
+ * KV arena
+ *
+ * Storage.  The arena holds n_pages K pages followed by n_pages V pages.  A
+ * page holds RLHF_PAGE_TOKENS tokens of every KV head; the part of a page that
+ * belongs to one head is a "block" of 16*head_dim elements, and block
+ * (page, head) starts at element (page*n_kv_heads + head)*16*head_dim of the K
+ * (or V) half.  Inside a block the elements are stored in the order in which
+ * one 64-lane wavefront consumes them, so that every 1 KiB a wavefront loads
+ * is contiguous and is already a matrix-core operand:
+ *
+ *   K block: element (slot s, dim d) at offset ((d/8)*16 + s)*8 + d%8
+ *            -- 16-byte granules of 8 consecutive dims, granules of the 16
+ *            slots adjacent, then the next 8 dims;
+ *   V block: element (slot s, dim d) at offset ((s/4)*head_dim + d)*4 + s%4
+ *            -- 8-byte granules of 4 consecutive slots at one dim, granules of
+ *            consecutive dims adjacent, then the next 4 slots.
+ *
+ * Callers never need this layout: rlhf_kv_arena_append writes it and
+ * rlhf_kv_arena_gather reads it back in plain [token][head][dim] order.
+ *
+ * Bookkeeping (all integer, exact).  Pages are popped from the head of a free
+ * list that starts as initial_free_order.  A sequence takes a new page exactly
+ * when its length is a multiple of 16.  rlhf_kv_arena_free_seq pushes the
+ * sequence's pages to the tail of the free list in logical order;
+ * rlhf_kv_arena_reset restores initial_free_order.  reset is the arena's
+ * counterpart of the cache release the paper inserts after each phase
+ * (Section 3.3), at the cost of host integer work only.
+ * ------------------------------------------------------------------------ */
+
+typedef struct rlhf_kv_arena rlhf_kv_arena; /* opaque, library-owned */
+
+/* flags for rlhf_kv_arena_desc.flags */
+#define RLHF_ARENA_HOST_ONLY 1u /* bookkeeping only: no device is touched, append ignores
+                                   k_new/v_new, views/gather are unavailable */
+
+typedef struct {
+    int32_t max_seqs;          /* sequence ids are 0 .. max_seqs-1 */
+    int32_t n_kv_heads;
+    int32_t head_dim;          /* 64 or 128 */
+    int32_t page_tokens;       /* must be RLHF_PAGE_TOKENS */
+    int32_t n_pages;           /* pages in the arena (each has a K part and a V part) */
+    int32_t max_pages_per_seq; /* row length of the page table */
+    int32_t kv_dtype;          /* RLHF_F16 or RLHF_BF16 */
+    uint32_t flags;
+    void *device_buffer;       /* dev, 256-byte aligned, caller-owned; NULL: the library
+                                  makes the one allocation itself */
+    size_t device_buffer_bytes;/* must be >= rlhf_kv_arena_bytes_required */
+    const int32_t *initial_free_order; /* host, a permutation of 0..n_pages-1; NULL: identity */
+} rlhf_kv_arena_desc;
+
+/* Bytes of K/V storage the description needs (2 * n_pages * page bytes). */
+int rlhf_kv_arena_bytes_required(const rlhf_kv_arena_desc *desc, size_t *out_bytes);
+
+/* Creates the arena.  Besides the K/V storage it allocates, once, the device
+ * page table [max_seqs][max_pages_per_seq] (int32, unused entries -1), the
+ * device lengths [max_seqs] (int32) and a small pinned command ring.  Nothing
+ * is allocated afterwards.  Synchronises the device once. */
+int rlhf_kv_arena_create(const rlhf_kv_arena_desc *desc, rlhf_kv_arena **out);
+
+/* Waits for the device, then frees everything the library allocated. */
+int rlhf_kv_arena_destroy(rlhf_kv_arena *arena);
+
+/* Appends n_new[i] tokens to sequence seq_ids[i], i = 0 .. n_seqs-1, in that
+ * order.  k_new / v_new (dev) hold the new rows packed as [sum n_new][n_kv_heads]
+ * [head_dim] in the arena's dtype, sequence after sequence.  A sequence id may
+ * appear once per call.  All-or-nothing: if the free list is too short the call
+ * returns RLHF_ERR_OOM, and if a sequence would outgrow max_pages_per_seq it
+ * returns RLHF_ERR_INVALID; in both cases nothing has changed.  The host
+ * mirrors are updated before return; the device page table, lengths and K/V
+ * pages are updated in stream order. */
+int rlhf_kv_arena_append(rlhf_kv_arena *arena, const int32_t *seq_ids /*host*/,
+                         const int32_t *n_new /*host*/, int32_t n_seqs,
+                         const void *k_new /*dev*/, const void *v_new /*dev*/, void *stream);
+
+/* Returns the pages of one sequence to the free-list tail; length becomes 0.
+ * Device mirrors are updated in stream order. */
+int rlhf_kv_arena_free_seq(rlhf_kv_arena *arena, int32_t seq_id, void *stream);
+
+/* Phase boundary: every page free again in initial_free_order, every length 0. */
+int rlhf_kv_arena_reset(rlhf_kv_arena *arena, void *stream);
+
+/* The paper's allocator counters (Section 2.2) for the arena. */
+typedef struct {
+    uint64_t reserved_bytes;    /* K/V storage taken at create; constant */
+    uint64_t allocated_bytes;   /* pages in use * page bytes, K and V */
+    uint64_t live_token_bytes;  /* bytes of tokens actually cached */
+    uint64_t driver_allocations;/* calls to the driver for K/V storage since create: 1 if the
+                                   library allocated the buffer, 0 if the caller brought it */
+    int32_t pages_free;
+    int32_t pages_in_use;
+    int32_t peak_pages_in_use;  /* since create or the last reset */
+    int32_t live_seqs;          /* sequences with length > 0 */
+} rlhf_kv_arena_stats_t;
+
+int rlhf_kv_arena_stats(const rlhf_kv_arena *arena, rlhf_kv_arena_stats_t *out);
+
+/* Device views for rlhf_decode_attention.  Pointers stay valid until destroy. */
+int rlhf_kv_arena_views(const rlhf_kv_arena *arena, const void **k_arena, const void **v_arena,
+                        const int32_t **page_table /*dev [max_seqs][max_pages_per_seq]*/,
+                        const int32_t **seq_lens /*dev [max_seqs]*/);
+
+/* Host mirrors of the bookkeeping (valid until the next call on the arena):
+ * page table [max_seqs][max_pages_per_seq] with -1 in unused entries, lengths
+ * [max_seqs], and the free list (free_count entries, head first). */
+int rlhf_kv_arena_host_state(const rlhf_kv_arena *arena, const int32_t **page_table,
+                             const int32_t **seq_lens, const int32_t **free_list,
+                             int32_t *free_count);
+
+/* Reads tokens [start, start+n) of a sequence back as plain rows: k_out / v_out
+ * (dev) receive [n][n_kv_heads][head_dim] in the arena's dtype. */
+int rlhf_kv_arena_gather(const rlhf_kv_arena *arena, int32_t seq_id, int32_t start, int32_t n,
+                         void *k_out /*dev*/, void *v_out /*dev*/, void *stream);
+
+/* ------------------------------------------------------------------------
+ * Decode attention (Section 2.1: the actor generating one token per step).
+ *
+ * For every sequence b and query head h, with kv head h / (n_q_heads /
+ * n_kv_heads) and L = seq_lens[b] cached tokens (the current token's K/V has
+ * been appended already, so causality needs no mask):
+ *     s_j = softmax_scale * <q[b,h,:], K_j>,  j = 0 .. L-1
+ *     out[b,h,:] = sum_j softmax(s)_j * V_j
+ * computed as a split over the token range with an online softmax per split
+ * and a log-sum-exp merge; fp32 accumulation.  L = 0 gives zeros.  Lengths
+ * above max_seq_len are treated as max_seq_len.
+ *
+ *   q          dev [batch][n_q_heads][head_dim], qkv_dtype
+ *   k_arena    dev, K half of an arena in the block layout above
+ *   v_arena    dev, V half
+ *   page_table dev [batch][max_pages_per_seq] int32
+ *   seq_lens   dev [batch] int32
+ *   out        dev [batch][n_q_heads][head_dim], out_dtype (round to nearest even)
+ *   workspace  dev, >= rlhf_decode_attention_workspace_bytes, 16-byte aligned;
+ *              scratch for split partials, contents undefined afterwards
+ * q, k_arena, v_arena and out must be 16-byte aligned.
+ * ------------------------------------------------------------------------ */
+typedef struct {
+    int32_t batch;
+    int32_t n_q_heads;
+    int32_t n_kv_heads;        /* divides n_q_heads */
+    int32_t head_dim;          /* 64 or 128 */
+    int32_t page_tokens;       /* RLHF_PAGE_TOKENS */
+    int32_t max_pages_per_seq; /* row length of page_table */
+    int32_t max_seq_len;       /* upper bound on seq_lens; 0: max_pages_per_seq*page_tokens.
+                                  Sizes the launch and the workspace. */
+    int32_t qkv_dtype;         /* RLHF_F16 or RLHF_BF16 */
+    int32_t out_dtype;         /* qkv_dtype or RLHF_F32 */
+    float softmax_scale;       /* 0: 1/sqrt(head_dim) */
+} rlhf_attn_params;
+
+int rlhf_decode_attention_workspace_bytes(const rlhf_attn_params *params, size_t *out_bytes);
+
+int rlhf_decode_attention(const rlhf_attn_params *params, const void *q, const void *k_arena,
+                          const void *v_arena, const int32_t *page_table, const int32_t *seq_lens,
+                          void *out, void *workspace, size_t workspace_bytes, void *stream);
+
+/* ------------------------------------------------------------------------
+ * Fused token log-probability and actor-vs-reference KL (Section 2.1: actor
+ * and reference inferences over the generated tokens; "minimizing policy
+ * deviation").  For each position i, in one pass over the two logit rows:
+ *     logp_out[i] = log softmax(actor[i,:])[tokens[i]]
+ *     kl_out[i]   = KL( softmax(actor[i,:]) || softmax(ref[i,:]) )   (nats, >= 0 up to rounding)
+ * fp32 accumulation.  tokens[i] outside [0, vocab) marks padding: both
+ * outputs are 0 for that position.
+ *
+ *   actor_logits, ref_logits  dev [n_positions][row_stride_elems], logits_dtype
+ *                             (RLHF_F32 or RLHF_BF16 or RLHF_F16); first `vocab` entries of a row used
+ *   tokens                    dev [n_positions] int32
+ *   logp_out, kl_out          dev [n_positions] float
+ *   row_stride_elems          0: vocab
+ * Rows that start 16-byte aligned take the vectorised path; others a slower
+ * element-wise one with the same results up to summation order.
+ * ------------------------------------------------------------------------ */
+int rlhf_token_logprobs_kl(const void *actor_logits, const void *ref_logits, const int32_t *tokens,
+                           float *logp_out, float *kl_out, int64_t n_positions, int32_t vocab,
+                           int64_t row_stride_elems, int32_t logits_dtype, void *stream);
+
+/* Text for the most recent failure on this thread ("" if none). */
+const char *rlhf_last_error_string(void);
+
+/* Library version, for the binding's sanity check. */
+int rlhf_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RLHF_ROLLOUT_H */

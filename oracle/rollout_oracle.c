@@ -1,0 +1,247 @@
+/*
+ * rollout_oracle.c -- TEST INFRASTRUCTURE, not product code.
+ *
+ * A plain, slow, fp64 CPU statement of what the rollout hot path computes, used
+ * only to check the GPU library and to be timed beside it as a baseline.  It
+ * shares no source, header, table or helper with the GPU library and is never
+ * called by it.
+ *
+ * The paper (Section 2.1, "RLHF Training") says which quantities exist in the
+ * experience-generation step of PPO stage 3 -- the actor generates responses
+ * token by token, and actor and reference inferences over the generated
+ * sequences feed a penalty on policy deviation -- but prints no formula for
+ * any of them.  Each function below is therefore the textbook definition
+ * written out:
+ *
+ *   oracle_decode_attention   softmax(scale * q.K^T) V for one query token per
+ *                             sequence over a paged key/value cache
+ *   oracle_token_logprobs_kl  log-softmax of the actor logits gathered at the
+ *                             sampled token, and KL(actor || reference) over
+ *                             the whole vocabulary
+ *
+ * Inputs arrive in their storage precision (IEEE binary16, bfloat16 or
+ * binary32) and are widened exactly to double; every sum, exponential and
+ * logarithm is in double.  Loops run in logical order with a separate pass for
+ * the maximum: no tiling, no online rescaling, no fused algebra.  OpenMP only
+ * distributes independent outputs over host threads.
+ *
+ * Every function here is pinned by tests that do not go through this file's
+ * own formulas (closed forms, brute force, library routines, invariants).
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+enum { ORACLE_F16 = 0, ORACLE_BF16 = 1, ORACLE_F32 = 2 };
+
+/* IEEE 754 binary16 -> double, from the format definition: 1 sign bit, 5
+ * exponent bits (bias 15), 10 fraction bits; exponent 0 is subnormal, 31 is
+ * inf/NaN. */
+static double widen_f16(uint16_t h)
+{
+    int sign = (h >> 15) & 1;
+    int e = (h >> 10) & 0x1f;
+    int f = h & 0x3ff;
+    double v;
+    if (e == 0)
+        v = ldexp((double)f, -24);
+    else if (e == 31)
+        v = f ? NAN : INFINITY;
+    else
+        v = ldexp((double)(f | 0x400), e - 25);
+    return sign ? -v : v;
+}
+
+/* bfloat16 is the upper half of a binary32. */
+static double widen_bf16(uint16_t b)
+{
+    uint32_t u = (uint32_t)b << 16;
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return (double)f;
+}
+
+static double load_elem(const void *base, size_t idx, int dtype)
+{
+    switch (dtype) {
+    case ORACLE_F16:
+        return widen_f16(((const uint16_t *)base)[idx]);
+    case ORACLE_BF16:
+        return widen_bf16(((const uint16_t *)base)[idx]);
+    default:
+        return (double)((const float *)base)[idx];
+    }
+}
+
+int oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/*
+ * Single-token decode attention over a paged cache (Section 2.1: the actor
+ * generating a response one token at a time; the definition is the standard
+ * scaled dot-product attention with one query row).
+ *
+ *   q          [B][Hq][D]                      storage dtype
+ *   k_pages    [n_pages][Hkv][P][D]            storage dtype, plain token-major pages
+ *   v_pages    same shape
+ *   page_table [B][max_pages]  physical page of logical page i of sequence b
+ *   seq_lens   [B]             cached tokens, the current one included
+ *   out        [B][Hq][D]      double
+ *
+ * Query head hq reads KV head hq / (Hq / Hkv).  Token j of sequence b lives at
+ * page page_table[b][j / P], slot j % P.  For each (b, hq):
+ *   s_j = scale * sum_d q_d K_jd ;  m = max_j s_j ;  w_j = exp(s_j - m)
+ *   out = (sum_j w_j V_j) / (sum_j w_j)
+ * A sequence of length 0 yields zeros.  weights_out, if not NULL, receives the
+ * normalised weights w_j / sum w for (b, hq) in a [B][Hq][max_pages*P] array
+ * (entries past the length are left untouched); tests use it for the
+ * rows-sum-to-one pin.
+ */
+int oracle_decode_attention(const void *q, const void *k_pages, const void *v_pages,
+                            const int32_t *page_table, const int32_t *seq_lens,
+                            double *out, double *weights_out,
+                            int B, int Hq, int Hkv, int D, int P, int max_pages,
+                            int dtype, double scale)
+{
+    if (!q || !k_pages || !v_pages || !page_table || !seq_lens || !out)
+        return -1;
+    if (B < 0 || Hq <= 0 || Hkv <= 0 || D <= 0 || P <= 0 || max_pages < 0 || Hq % Hkv)
+        return -1;
+    const int G = Hq / Hkv;
+    const size_t page_elems = (size_t)Hkv * P * D;
+    int bad = 0;
+
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b) {
+        for (int hq = 0; hq < Hq; ++hq) {
+            const int L = seq_lens[b];
+            const int hkv = hq / G;
+            double *o = out + ((size_t)b * Hq + hq) * D;
+            for (int d = 0; d < D; ++d)
+                o[d] = 0.0;
+            if (L < 0 || L > max_pages * P) {
+#pragma omp atomic write
+                bad = 1;
+                continue;
+            }
+            if (L == 0)
+                continue;
+            const size_t qbase = ((size_t)b * Hq + hq) * D;
+
+            /* pass 1: the largest score */
+            double m = -INFINITY;
+            for (int j = 0; j < L; ++j) {
+                const size_t page = (size_t)page_table[(size_t)b * max_pages + j / P];
+                const size_t row = page * page_elems + ((size_t)hkv * P + j % P) * D;
+                double s = 0.0;
+                for (int d = 0; d < D; ++d)
+                    s += load_elem(q, qbase + d, dtype) * load_elem(k_pages, row + d, dtype);
+                s *= scale;
+                if (s > m)
+                    m = s;
+            }
+            /* pass 2: weights, their sum, and the weighted sum of value rows */
+            double denom = 0.0;
+            for (int j = 0; j < L; ++j) {
+                const size_t page = (size_t)page_table[(size_t)b * max_pages + j / P];
+                const size_t row = page * page_elems + ((size_t)hkv * P + j % P) * D;
+                double s = 0.0;
+                for (int d = 0; d < D; ++d)
+                    s += load_elem(q, qbase + d, dtype) * load_elem(k_pages, row + d, dtype);
+                s *= scale;
+                const double w = exp(s - m);
+                denom += w;
+                for (int d = 0; d < D; ++d)
+                    o[d] += w * load_elem(v_pages, row + d, dtype);
+                if (weights_out)
+                    weights_out[((size_t)b * Hq + hq) * ((size_t)max_pages * P) + j] = w;
+            }
+            for (int d = 0; d < D; ++d)
+                o[d] /= denom;
+            if (weights_out)
+                for (int j = 0; j < L; ++j)
+                    weights_out[((size_t)b * Hq + hq) * ((size_t)max_pages * P) + j] /= denom;
+        }
+    }
+    return bad ? -1 : 0;
+}
+
+/*
+ * Per-position log-probability of the sampled token under the actor, and the
+ * KL divergence of the actor's next-token distribution from the reference
+ * model's (Section 2.1: the reference model restrains the policy; the actor is
+ * trained while "minimizing policy deviation").  Natural logarithms.
+ *
+ *   actor, ref  [N][stride] rows, first V entries of each row used; storage dtype
+ *   tokens      [N]
+ *   logp, kl    [N] double
+ *
+ * For row i:
+ *   lse_a = m_a + log sum_v exp(a_v - m_a),  m_a = max_v a_v     (same for r)
+ *   logp  = a_tok - lse_a
+ *   kl    = sum_v p_v * ((a_v - lse_a) - (r_v - lse_r)),  p_v = exp(a_v - lse_a)
+ * The KL is summed term by term from its definition.  A term with p_v == 0
+ * counts as 0 (so an actor logit of -inf never produces 0 * inf).
+ * tokens[i] < 0 or >= V marks a padded position: logp = kl = 0 for it.
+ */
+int oracle_token_logprobs_kl(const void *actor, const void *ref, const int32_t *tokens,
+                             double *logp, double *kl,
+                             int64_t N, int V, int64_t stride, int dtype)
+{
+    if (!actor || !ref || !tokens || !logp || !kl || N < 0 || V <= 0)
+        return -1;
+    if (stride == 0)
+        stride = V;
+    if (stride < V)
+        return -1;
+
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < N; ++i) {
+        const int32_t tok = tokens[i];
+        if (tok < 0 || tok >= V) {
+            logp[i] = 0.0;
+            kl[i] = 0.0;
+            continue;
+        }
+        const size_t base = (size_t)i * (size_t)stride;
+
+        double ma = -INFINITY, mr = -INFINITY;
+        for (int v = 0; v < V; ++v) {
+            const double a = load_elem(actor, base + v, dtype);
+            const double r = load_elem(ref, base + v, dtype);
+            if (a > ma)
+                ma = a;
+            if (r > mr)
+                mr = r;
+        }
+        double sa = 0.0, sr = 0.0;
+        for (int v = 0; v < V; ++v) {
+            sa += exp(load_elem(actor, base + v, dtype) - ma);
+            sr += exp(load_elem(ref, base + v, dtype) - mr);
+        }
+        const double lse_a = ma + log(sa);
+        const double lse_r = mr + log(sr);
+
+        double acc = 0.0;
+        for (int v = 0; v < V; ++v) {
+            const double la = load_elem(actor, base + v, dtype) - lse_a; /* log p_v */
+            const double lr = load_elem(ref, base + v, dtype) - lse_r;   /* log q_v */
+            const double p = exp(la);
+            if (p > 0.0)
+                acc += p * (la - lr);
+        }
+        logp[i] = load_elem(actor, base + (size_t)tok, dtype) - lse_a;
+        kl[i] = acc;
+    }
+    return 0;
+}
