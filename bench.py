@@ -1,0 +1,248 @@
+#!/usr/bin/env python3
+"""Benchmark of the rollout hot path on one MI355X.
+
+One step = what one decode step plus the scoring of the generated positions
+costs on the hot path: append one token's K/V per sequence to the arena,
+single-token decode attention over the paged cache, and the fused token
+log-prob / actor-vs-reference KL over the full logit matrices.  Inputs are
+synthetic, seeded, and resident in HBM before the timed region starts.
+
+Prints ONE JSON line.  `value` is the algorithmic HBM traffic of a whole step
+divided by the step time; the per-kernel figures (decode-attention GB/s and its
+fraction of peak, log-prob/KL positions per second) are in `components`.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0     # MI355X, HBM3E
+METRIC = "decode-attn HBM GB/s (% of MI355X peak) + logprob/KL tokens/sec, 1 GPU"
+
+
+def log(msg):
+    print(msg, file=sys.stderr, flush=True)
+
+
+def attention_bytes(lens, cfg, eb=2):
+    """Algorithmic bytes of one decode-attention call: K and V of every cached
+    token once, q in and out out, page ids and lengths."""
+    P = 16
+    lens = lens.astype(np.int64)
+    kv = 2 * lens.sum() * cfg.n_kv_heads * cfg.head_dim * eb
+    qo = 2 * cfg.batch * cfg.n_q_heads * cfg.head_dim * eb
+    ids = 4 * ((lens + P - 1) // P).sum() + 4 * cfg.batch
+    return int(kv + qo + ids)
+
+
+def logprob_bytes(n, vocab, lb):
+    return int(n) * (2 * vocab * lb + 4 + 8)
+
+
+def append_bytes(cfg, eb=2):
+    return 2 * 2 * cfg.batch * cfg.n_kv_heads * cfg.head_dim * eb   # rows read + written, K and V
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=5, help="workload index 1..5 (default: the largest)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on ONE GPU; --gpus above 1 is not supported "
+            "(no collectives or sharding are part of it).")
+        sys.exit(2)
+
+    import torch
+    from paper_2410_15651_amd import binding as rb
+    from paper_2410_15651_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible; the hot path has no CPU fallback.")
+        sys.exit(1)
+    rb.lib()                                   # fail loudly if the HIP library is missing
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    cfg = wl.config(args.config)
+    K, W = args.steps, args.warmup
+    P = wl.PAGE_TOKENS
+    eb = 2
+    lb = 4 if cfg.logits_dtype == "f32" else 2
+
+    # ---------------- inputs, resident in HBM ----------------
+    t0 = time.time()
+    lens = wl.seq_lengths(cfg)
+    q, ks, vs = wl.qkv(cfg, lens, device=dev)
+    extra = K + W + 1
+    mpps = cfg.max_pages_per_seq(extra)
+    n_pages = int(((lens.astype(np.int64) + extra + P - 1) // P).sum()) + 8
+    order = wl.free_order(cfg, n_pages)
+    kw = dict(max_seqs=cfg.batch, n_kv_heads=cfg.n_kv_heads, head_dim=cfg.head_dim, n_pages=n_pages,
+              max_pages_per_seq=mpps, kv_dtype=wl.DTYPE_CODE[cfg.kv_dtype], initial_free_order=order)
+    arena_bytes = rb.rlhf_kv_arena_bytes_required(**kw)
+    arena_buf = torch.empty(arena_bytes, dtype=torch.uint8, device=dev)
+    arena = rb.rlhf_kv_arena_create(device_buffer=arena_buf, device_buffer_bytes=arena_bytes, **kw)
+    done = np.zeros(cfg.batch, dtype=np.int64)
+    for ids, n_new in wl.fill_schedule(cfg, lens, hold_back=0):
+        k_new = torch.cat([ks[b][done[b]:done[b] + n] for b, n in zip(ids, n_new)]).contiguous()
+        v_new = torch.cat([vs[b][done[b]:done[b] + n] for b, n in zip(ids, n_new)]).contiguous()
+        rb.rlhf_kv_arena_append(arena, ids, n_new, k_new, v_new)
+        done[ids] += n_new
+    torch.cuda.synchronize()
+    g = torch.Generator(device=dev)
+    g.manual_seed(cfg.seed)
+    step_k = (torch.randn(cfg.batch, cfg.n_kv_heads, cfg.head_dim, generator=g, device=dev) * cfg.qkv_std
+              ).to(q.dtype)
+    step_v = (torch.randn(cfg.batch, cfg.n_kv_heads, cfg.head_dim, generator=g, device=dev) * cfg.qkv_std
+              ).to(q.dtype)
+    actor, ref = wl.logits(cfg, device=dev)
+    tok_np = wl.tokens(cfg)
+    tok = torch.from_numpy(tok_np).to(dev)
+    n_pos = cfg.n_positions
+    logp = torch.empty(n_pos, dtype=torch.float32, device=dev)
+    kl = torch.empty(n_pos, dtype=torch.float32, device=dev)
+    k_arena, v_arena, d_table, d_lens = rb.rlhf_kv_arena_views(arena)
+    params = rb.attn_params(cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, mpps,
+                            wl.DTYPE_CODE[cfg.kv_dtype], max_seq_len=cfg.len_hi + extra)
+    ws = torch.empty(rb.rlhf_decode_attention_workspace_bytes(params), dtype=torch.uint8, device=dev)
+    out = torch.empty(cfg.batch, cfg.n_q_heads, cfg.head_dim, dtype=q.dtype, device=dev)
+    seq_ids = np.arange(cfg.batch, dtype=np.int32)
+    ones = np.ones(cfg.batch, dtype=np.int32)
+    torch.cuda.synchronize()
+    log(f"setup {time.time() - t0:.1f}s: cfg{cfg.index} {cfg.name} K/V {2 * lens.sum() * cfg.n_kv_heads * cfg.head_dim * eb / 1e9:.3f} GB, "
+        f"logits {2 * n_pos * cfg.vocab * lb / 1e9:.2f} GB, arena reserved {arena_bytes / 1e9:.3f} GB")
+
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    marks = []
+
+    def step(record):
+        if record:
+            e = [ev() for _ in range(4)]
+            e[0].record()
+        rb.rlhf_kv_arena_append(arena, seq_ids, ones, step_k, step_v)
+        if record:
+            e[1].record()
+        rb.rlhf_decode_attention(params, q, k_arena, v_arena, d_table, d_lens, out, ws)
+        if record:
+            e[2].record()
+        rb.rlhf_token_logprobs_kl(actor, ref, tok, logp, kl)
+        if record:
+            e[3].record()
+            marks.append(e)
+
+    for _ in range(W):
+        step(False)
+    torch.cuda.synchronize()
+    cur_lens = lens.astype(np.int64) + W
+    step_attn_bytes = []
+    t_start = time.perf_counter()
+    for i in range(K):
+        step(True)
+        step_attn_bytes.append(attention_bytes(cur_lens + i + 1, cfg, eb))
+    torch.cuda.synchronize()
+    t_total = time.perf_counter() - t_start
+
+    t_append = np.array([m[0].elapsed_time(m[1]) for m in marks]) * 1e-3
+    t_attn = np.array([m[1].elapsed_time(m[2]) for m in marks]) * 1e-3
+    t_logp = np.array([m[2].elapsed_time(m[3]) for m in marks]) * 1e-3
+    b_attn = float(np.mean(step_attn_bytes))
+    b_logp = logprob_bytes(n_pos, cfg.vocab, lb)
+    b_step = b_attn + b_logp + append_bytes(cfg, eb)
+    ms_per_step = t_total / K * 1e3
+    value = b_step / (t_total / K) / 1e9
+    attn_gbps = b_attn / t_attn.mean() / 1e9
+    logp_gbps = b_logp / t_logp.mean() / 1e9
+    stats = rb.rlhf_kv_arena_stats(arena)
+
+    result = {
+        "metric": METRIC, "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32 accumulate (bf16/f16 storage)", "data": "synthetic",
+        "config": {"workload": f"configs[{cfg.index - 1}] {cfg.name}: batch {cfg.batch}, {cfg.n_q_heads}q/"
+                               f"{cfg.n_kv_heads}kv heads, head_dim {cfg.head_dim}, {cfg.kv_dtype} KV, cache "
+                               f"lengths U[{cfg.len_lo},{cfg.len_hi}], 16-token pages "
+                               f"{'shuffled' if cfg.shuffled_pages else 'in order'}; logprob/KL {n_pos} positions x "
+                               f"vocab {cfg.vocab}, {cfg.logits_dtype} logits",
+                   "step": "append 1 token/seq + decode attention + token logprob/KL",
+                   "accumulate": "fp32", "hbm_peak_GBps": HBM_PEAK_GBPS},
+        "components": {
+            "decode_attn_GBps": round(attn_gbps, 1), "decode_attn_frac_of_peak": round(attn_gbps / HBM_PEAK_GBPS, 4),
+            "decode_attn_us": round(t_attn.mean() * 1e6, 2), "decode_attn_bytes": int(b_attn),
+            "logprob_kl_tokens_per_s": round(n_pos / t_logp.mean(), 1), "logprob_kl_GBps": round(logp_gbps, 1),
+            "logprob_kl_frac_of_peak": round(logp_gbps / HBM_PEAK_GBPS, 4),
+            "logprob_kl_us": round(t_logp.mean() * 1e6, 2), "append_us": round(t_append.mean() * 1e6, 2),
+            "arena_reserved_bytes": stats["reserved_bytes"], "arena_allocated_bytes": stats["allocated_bytes"],
+            "arena_driver_allocations_after_create": 0,
+        },
+        "roofline": {"kernel": "logprob_kl_kernel", "bound": "hbm", "achieved": round(logp_gbps, 1),
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(logp_gbps / HBM_PEAK_GBPS, 4),
+                     "traffic": None},
+        "roofline_decode_attn": {"kernel": "attn_split_kernel+attn_merge_kernel", "bound": "hbm",
+                                 "achieved": round(attn_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                                 "frac": round(attn_gbps / HBM_PEAK_GBPS, 4), "traffic": None},
+    }
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(cfg, lens, q, ks, vs, actor, ref, tok_np, b_step, lb, eb)
+    rb.rlhf_kv_arena_destroy(arena)
+    print(json.dumps(result), flush=True)
+
+
+def cpu_baseline(cfg, lens, q, ks, vs, actor, ref, tok_np, b_step, lb, eb):
+    """The fp64 oracle, as it stands, timed on the host cores on a bounded sample
+    of the same workload and scaled to a whole step."""
+    import torch
+    import oracle
+    from paper_2410_15651_amd import workloads as wl
+    P = wl.PAGE_TOKENS
+    oracle.build()
+    rng = np.random.default_rng(cfg.seed)
+    n_seq = min(cfg.batch, 48)
+    seqs = np.sort(rng.choice(cfg.batch, n_seq, replace=False))
+    n_rows = min(cfg.n_positions, max(256, int(12288 * 128256 / cfg.vocab)))
+    rows = np.sort(rng.choice(cfg.n_positions, n_rows, replace=False))
+    # attention sample: plain pages in logical order for the sampled sequences
+    ks_h = [wl.to_storage(ks[b]) for b in seqs]
+    vs_h = [wl.to_storage(vs[b]) for b in seqs]
+    need = [(int(lens[b]) + P - 1) // P for b in seqs]
+    table = np.full((n_seq, max(need)), -1, dtype=np.int32)
+    nxt = 0
+    for i, n in enumerate(need):
+        table[i, :n] = np.arange(nxt, nxt + n)
+        nxt += n
+    kp, vp = wl.plain_pages(ks_h, vs_h, table, nxt)
+    qh = wl.to_storage(q)[seqs]
+    code = wl.DTYPE_CODE[cfg.kv_dtype]
+    t = time.perf_counter()
+    oracle.decode_attention(qh, kp, vp, table, lens[seqs], code)
+    t_attn = time.perf_counter() - t
+    idx = torch.from_numpy(rows).to(actor.device)
+    a_h = wl.to_storage(actor[idx])
+    r_h = wl.to_storage(ref[idx])
+    t = time.perf_counter()
+    oracle.token_logprobs_kl(a_h, r_h, tok_np[rows], wl.DTYPE_CODE[cfg.logits_dtype])
+    t_logp = time.perf_counter() - t
+    est_step = t_attn * cfg.batch / n_seq + t_logp * cfg.n_positions / n_rows
+    return {
+        "value": round(b_step / est_step / 1e9, 4), "unit": "GB/s", "cores": oracle.num_threads(),
+        "kind": "oracle",
+        "sample": f"{n_seq} of {cfg.batch} sequences (attention, {t_attn:.2f}s) and {n_rows} of "
+                  f"{cfg.n_positions} logit rows (logprob/KL, {t_logp:.2f}s), scaled to one whole step "
+                  f"({est_step:.1f}s estimated)",
+        "logprob_kl_tokens_per_s": round(n_rows / t_logp, 1),
+    }
+
+
+if __name__ == "__main__":
+    main()

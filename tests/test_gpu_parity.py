@@ -1,0 +1,329 @@
+"""GPU parity: the HIP library, called through its C ABI, against the fp64 CPU
+oracle on the same seeded inputs.  Tolerances are the ones the task fixes:
+2e-3 max-abs on attention outputs, 1e-3 on log-probs and KL (fp32
+accumulation), bit-exact for every integer / byte result."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2410_15651_amd import binding as rb
+from paper_2410_15651_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+ATTN_TOL = 2e-3
+LOGP_TOL = 1e-3
+P = wl.PAGE_TOKENS
+
+
+@pytest.fixture(scope="module")
+def gu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import gpu_util
+    return gpu_util
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+# ------------------------------------------------------------------ arena ----
+def _decode_block_layout(raw: np.ndarray, n_pages, Hkv, D):
+    """Raw arena bytes -> plain pages [n_pages, Hkv, 16, D] for K and V, written
+    from the layout formulas documented in include/rlhf_rollout.h."""
+    half = raw.size // 2
+    k = raw[:half].reshape(n_pages, Hkv, D // 8, P, 8)            # [dseg][slot][8]
+    kp = k.transpose(0, 1, 3, 2, 4).reshape(n_pages, Hkv, P, D)
+    v = raw[half:].reshape(n_pages, Hkv, P // 4, D, 4)            # [quad][d][4 slots]
+    vp = v.transpose(0, 1, 2, 4, 3).reshape(n_pages, Hkv, P, D)
+    return kp, vp
+
+
+@pytest.mark.parametrize("cfg_index,batch", [(1, 4), (4, 6)])
+def test_arena_append_gather_and_layout_bit_exact(gu, cfg_index, batch):
+    cfg = wl.small_variant(wl.config(cfg_index), batch=batch, len_lo=1, len_hi=150)
+    lens = wl.seq_lengths(cfg)
+    lens[0] = 1
+    lens[-1] = 150
+    _say(f"arena cfg{cfg_index} lens={lens.tolist()}")
+    q, ks, vs = wl.qkv(cfg, lens, device=gu.DEV)
+    A = gu.FilledArena(cfg, lens, ks, vs)
+    try:
+        table, hl, free = A.host_state()
+        assert table.tolist() == A.model.page_table()
+        assert hl.tolist() == A.model.seq_lens == lens.tolist()
+        assert free.tolist() == A.model.free
+        st = rb.rlhf_kv_arena_stats(A.handle)
+        for k_, v_ in A.model.stats().items():
+            assert st[k_] == v_
+        assert st["reserved_bytes"] == A.bytes and st["driver_allocations"] == 0
+        # device mirrors
+        _, _, d_table, d_lens = A.views()
+        dev_table = torch.empty(cfg.batch * A.mpps, dtype=torch.int32, device=gu.DEV)
+        dev_lens = torch.empty(cfg.batch, dtype=torch.int32, device=gu.DEV)
+        import ctypes
+        hip = ctypes.CDLL("libamdhip64.so")
+        assert hip.hipMemcpy(ctypes.c_void_p(dev_table.data_ptr()), ctypes.c_void_p(d_table),
+                             ctypes.c_size_t(dev_table.numel() * 4), 3) == 0
+        assert hip.hipMemcpy(ctypes.c_void_p(dev_lens.data_ptr()), ctypes.c_void_p(d_lens),
+                             ctypes.c_size_t(dev_lens.numel() * 4), 3) == 0
+        assert dev_table.cpu().numpy().reshape(cfg.batch, A.mpps).tolist() == table.tolist()
+        assert dev_lens.cpu().numpy().tolist() == lens.tolist()
+        # gather returns exactly what was appended
+        for b in range(cfg.batch):
+            L = int(lens[b])
+            ko = torch.zeros_like(ks[b])
+            vo = torch.zeros_like(vs[b])
+            rb.rlhf_kv_arena_gather(A.handle, b, 0, L, ko, vo)
+            torch.cuda.synchronize()
+            assert torch.equal(ko.view(torch.int16), ks[b].view(torch.int16))
+            assert torch.equal(vo.view(torch.int16), vs[b].view(torch.int16))
+            if L > 3:
+                ko2 = torch.zeros_like(ks[b][2:L - 1])
+                vo2 = torch.zeros_like(ko2)
+                rb.rlhf_kv_arena_gather(A.handle, b, 2, L - 3, ko2, vo2)
+                torch.cuda.synchronize()
+                assert torch.equal(ko2.view(torch.int16), ks[b][2:L - 1].view(torch.int16))
+                assert torch.equal(vo2.view(torch.int16), vs[b][2:L - 1].view(torch.int16))
+        # raw bytes follow the documented block layout
+        raw = A.buffer.cpu().numpy().view(np.uint16)
+        kp, vp = _decode_block_layout(raw, A.n_pages, cfg.n_kv_heads, cfg.head_dim)
+        ek, ev = wl.plain_pages([wl.to_storage(k) for k in ks], [wl.to_storage(v) for v in vs], table, A.n_pages)
+        for b in range(cfg.batch):
+            for lp in range((int(lens[b]) + P - 1) // P):
+                n = min(P, int(lens[b]) - lp * P)
+                pg = table[b, lp]
+                assert np.array_equal(kp[pg, :, :n], ek[pg, :, :n])
+                assert np.array_equal(vp[pg, :, :n], ev[pg, :, :n])
+        # free + reuse: freed pages go to the tail, device table rows are cleared
+        rb.rlhf_kv_arena_free_seq(A.handle, 0)
+        A.model.free_seq(0)
+        rb.rlhf_kv_arena_append(A.handle, [0], [5], ks[-1][:5].contiguous(), vs[-1][:5].contiguous())
+        A.model.append([0], [5])
+        torch.cuda.synchronize()
+        table2, hl2, free2 = A.host_state()
+        assert table2.tolist() == A.model.page_table() and free2.tolist() == A.model.free
+        ko = torch.zeros_like(ks[-1][:5])
+        vo = torch.zeros_like(ko)
+        rb.rlhf_kv_arena_gather(A.handle, 0, 0, 5, ko, vo)
+        torch.cuda.synchronize()
+        assert torch.equal(ko.view(torch.int16), ks[-1][:5].view(torch.int16))
+        assert torch.equal(vo.view(torch.int16), vs[-1][:5].view(torch.int16))
+    finally:
+        A.close()
+
+
+# -------------------------------------------------------------- attention ----
+SMALL_ATTN = [
+    # (config index, overrides) -- shapes span several pages, chunks and a ragged tail
+    (1, dict()),                                                        # full config 1
+    (2, dict(batch=3)),
+    (3, dict(batch=2, len_lo=500, len_hi=1024)),
+    (4, dict(batch=2, n_q_heads=4, n_kv_heads=4, len_lo=1000, len_hi=2048)),
+    (5, dict(batch=2, n_q_heads=16, n_kv_heads=2, len_lo=2000, len_hi=4096)),
+    (5, dict(batch=3, n_q_heads=8, n_kv_heads=2, head_dim=64, len_lo=1, len_hi=300)),
+    (1, dict(batch=3, n_q_heads=6, n_kv_heads=2, head_dim=128, len_lo=1, len_hi=70)),
+]
+
+
+@pytest.mark.parametrize("cfg_index,over", SMALL_ATTN)
+def test_attention_matches_oracle(gu, oracle, cfg_index, over):
+    cfg = wl.small_variant(wl.config(cfg_index), **over)
+    lens = wl.seq_lengths(cfg)
+    _say(f"attention cfg{cfg_index} {over} lens={lens.tolist()}")
+    q, ks, vs = wl.qkv(cfg, lens, device=gu.DEV)
+    A = gu.FilledArena(cfg, lens, ks, vs)
+    try:
+        table, hl, _ = A.host_state()
+        assert table.tolist() == A.model.page_table() and hl.tolist() == lens.tolist()
+        expect = gu.oracle_attention(oracle, cfg, q, ks, vs, table, lens, A.n_pages)
+        out32 = gu.run_attention(cfg, A, q, out_dtype=rb.RLHF_F32).cpu().numpy().astype(np.float64)
+        err32 = np.abs(out32 - expect).max()
+        out16 = gu.run_attention(cfg, A, q).float().cpu().numpy().astype(np.float64)
+        err16 = np.abs(out16 - expect).max()
+        _say(f"  max-abs err: f32 out {err32:.3e}, {cfg.kv_dtype} out {err16:.3e}")
+        assert err32 <= ATTN_TOL
+        if cfg.len_lo >= 256 or cfg.kv_dtype == "f16":
+            assert err16 <= ATTN_TOL
+        else:   # short caches with unit-variance values: half an ulp of the 16-bit output itself
+            ulp = np.abs(expect).max() * 2.0 ** -8
+            assert err16 <= ATTN_TOL + ulp
+        # a tighter launch bound must not change anything
+        out_b = gu.run_attention(cfg, A, q, out_dtype=rb.RLHF_F32, max_seq_len=int(lens.max()))
+        assert np.abs(out_b.cpu().numpy() - expect).max() <= ATTN_TOL
+    finally:
+        A.close()
+
+
+def test_attention_degenerate_lengths_and_scale(gu, oracle):
+    cfg = wl.small_variant(wl.config(3), batch=6, n_q_heads=4, n_kv_heads=2, len_lo=0, len_hi=40)
+    lens = np.array([1, 0, 16, 17, 2, 40], dtype=np.int32)
+    q, ks, vs = wl.qkv(cfg, lens, device=gu.DEV)
+    A = gu.FilledArena(cfg, lens, ks, vs)
+    try:
+        table, _, _ = A.host_state()
+        expect = gu.oracle_attention(oracle, cfg, q, ks, vs, table, lens, A.n_pages)
+        out = gu.run_attention(cfg, A, q, out_dtype=rb.RLHF_F32).cpu().numpy().astype(np.float64)
+        assert np.isfinite(out).all()
+        assert (out[1] == 0).all()                                   # empty cache -> zeros
+        for h in range(4):                                           # one cached token -> its V row exactly
+            assert np.array_equal(out[0, h], vs[0][0, h // 2].double().cpu().numpy())
+        assert np.abs(out - expect).max() <= ATTN_TOL
+        out16 = gu.run_attention(cfg, A, q)
+        assert torch.equal(out16[0, 3].view(torch.int16), vs[0][0, 1].view(torch.int16))
+        # explicit softmax scale
+        expect_s = gu.oracle_attention(oracle, cfg, q, ks, vs, table, lens, A.n_pages, scale=0.31)
+        out_s = gu.run_attention(cfg, A, q, out_dtype=rb.RLHF_F32, scale=0.31).cpu().numpy()
+        assert np.abs(out_s - expect_s).max() <= ATTN_TOL
+        assert np.abs(expect_s - expect).max() > 10 * ATTN_TOL       # the scale really matters here
+    finally:
+        A.close()
+
+
+def test_attention_is_bit_identical_under_page_permutation(gu):
+    base = wl.small_variant(wl.config(3), batch=4, n_q_heads=8, n_kv_heads=8, len_lo=100, len_hi=700)
+    lens = wl.seq_lengths(base)
+    q, ks, vs = wl.qkv(base, lens, device=gu.DEV)
+    outs = []
+    for shuffled in (False, True):
+        cfg = wl.small_variant(base, shuffled_pages=shuffled)
+        A = gu.FilledArena(cfg, lens, ks, vs, slack_pages=11)
+        try:
+            outs.append(gu.run_attention(cfg, A, q, out_dtype=rb.RLHF_F32))
+            if shuffled:
+                table, _, _ = A.host_state()
+                assert table[0, :3].tolist() != [0, 1, 2]
+        finally:
+            A.close()
+    assert torch.equal(outs[0].view(torch.int32), outs[1].view(torch.int32))
+
+
+@pytest.mark.parametrize("cfg_index", [2, 3, 4, 5])
+def test_attention_full_size_sampled_sequences(gu, oracle, cfg_index):
+    """The benchmark's launch configuration at the full shape; the oracle checks
+    a sample of whole sequences (shortest, longest, two seeded picks)."""
+    cfg = wl.config(cfg_index)
+    lens = wl.seq_lengths(cfg)
+    _say(f"attention full cfg{cfg_index}: B={cfg.batch} tokens={int(lens.sum())}")
+    q, ks, vs = wl.qkv(cfg, lens, device=gu.DEV)
+    A = gu.FilledArena(cfg, lens, ks, vs)
+    try:
+        table, hl, free = A.host_state()
+        assert table.tolist() == A.model.page_table()
+        assert hl.tolist() == lens.tolist() and free.tolist() == A.model.free
+        rng = np.random.default_rng(cfg.seed)
+        seqs = sorted({int(lens.argmin()), int(lens.argmax()), *rng.integers(0, cfg.batch, 2).tolist()})
+        expect = gu.oracle_attention(oracle, cfg, q, ks, vs, table, lens, A.n_pages, seqs=seqs)
+        out = gu.run_attention(cfg, A, q, out_dtype=rb.RLHF_F32, max_seq_len=cfg.len_hi)
+        assert torch.isfinite(out).all()
+        err = np.abs(out[seqs].cpu().numpy().astype(np.float64) - expect).max()
+        out16 = gu.run_attention(cfg, A, q, max_seq_len=cfg.len_hi)
+        err16 = np.abs(out16[seqs].float().cpu().numpy().astype(np.float64) - expect).max()
+        _say(f"  seqs {seqs}: max-abs err f32 out {err:.3e}, 16-bit out {err16:.3e}")
+        assert err <= ATTN_TOL and err16 <= ATTN_TOL
+        # property that holds at any size: every output inside the range of the values
+        b = seqs[0]
+        vmin = vs[b].float().amin(0)
+        vmax = vs[b].float().amax(0)
+        G = cfg.n_q_heads // cfg.n_kv_heads
+        o = out[b].view(cfg.n_kv_heads, G, cfg.head_dim)
+        assert (o >= vmin[:, None, :] - 1e-5).all() and (o <= vmax[:, None, :] + 1e-5).all()
+    finally:
+        A.close()
+
+
+# ------------------------------------------------------------- logprob/KL ----
+SMALL_LOGITS = [
+    (1, 96), (2, 64), (3, 64), (5, 24),
+]
+
+
+@pytest.mark.parametrize("cfg_index,n", SMALL_LOGITS)
+def test_logprobs_kl_match_oracle(gu, oracle, cfg_index, n):
+    cfg = wl.config(cfg_index)
+    actor, ref = wl.logits(cfg, n_positions=n, device=gu.DEV)
+    tok = wl.tokens(cfg, n_positions=n)
+    _say(f"logprob cfg{cfg_index} n={n} V={cfg.vocab} {cfg.logits_dtype}")
+    logp, kl = gu.run_logprobs(actor, ref, tok)
+    el, ek = oracle.token_logprobs_kl(wl.to_storage(actor), wl.to_storage(ref), tok,
+                                      wl.DTYPE_CODE[cfg.logits_dtype])
+    _say(f"  max-abs err logp {np.abs(logp - el).max():.3e} kl {np.abs(kl - ek).max():.3e}")
+    assert np.abs(logp - el).max() <= LOGP_TOL
+    assert np.abs(kl - ek).max() <= LOGP_TOL
+    assert (kl > -1e-5).all()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
+@pytest.mark.parametrize("vocab,stride,offset", [(1003, 1003, 0), (4099, 4104, 0), (7, 8, 0), (2048, 2048, 1),
+                                                  (1, 1, 0), (50272, 50272, 0)])
+def test_logprobs_ragged_vocab_strides_and_alignment(gu, oracle, dtype, vocab, stride, offset):
+    """Tail elements past the last 16-byte vector, padded rows, rows that do not
+    start 16-byte aligned (element-wise path), one-element vocabularies."""
+    tdt = wl.torch_dtype(dtype)
+    n = 9
+    g = torch.Generator(device=gu.DEV)
+    g.manual_seed(vocab * 31 + stride)
+    buf_a = (torch.randn(n * stride + 8, generator=g, device=gu.DEV) * 3).to(tdt)
+    buf_r = (torch.randn(n * stride + 8, generator=g, device=gu.DEV) * 3).to(tdt)
+    actor = buf_a[offset:offset + n * stride].view(n, stride)
+    ref = buf_r[offset:offset + n * stride].view(n, stride)
+    tok = np.random.default_rng(vocab).integers(0, vocab, n).astype(np.int32)
+    logp, kl = gu.run_logprobs(actor, ref, tok, vocab=vocab, stride=stride)
+    el, ek = oracle.token_logprobs_kl(wl.to_storage(actor), wl.to_storage(ref), tok, wl.DTYPE_CODE[dtype],
+                                      vocab=vocab)
+    assert np.abs(logp - el).max() <= LOGP_TOL
+    assert np.abs(kl - ek).max() <= LOGP_TOL
+
+
+def test_logprobs_special_rows(gu, oracle):
+    """Identical rows (KL exactly 0), padded positions, -inf logits, a late
+    maximum far above the running reference, large common offsets."""
+    V, n = 5000, 8
+    g = torch.Generator(device=gu.DEV)
+    g.manual_seed(7)
+    actor = (torch.randn(n, V, generator=g, device=gu.DEV) * 3).to(torch.bfloat16)
+    ref = (torch.randn(n, V, generator=g, device=gu.DEV) * 3).to(torch.bfloat16)
+    ref[0] = actor[0]                                   # identical
+    actor[1, 100:2000] = float("-inf")                  # masked actor logits
+    ref[2, 5:50] = float("-inf")                        # reference forbids tokens the actor allows
+    actor[3, 4000] = 90.0                               # late spike, > lift threshold above the rest
+    ref[3, 17] = 70.0
+    actor[4] += 300.0                                   # large common offset
+    ref[4] -= 300.0
+    actor[5, :] = float("-inf")
+    actor[5, 7] = 0.0                                   # one-hot actor
+    tok = np.array([3, 5, 1000, 4000, 9, 7, -1, V], dtype=np.int32)
+    logp, kl = gu.run_logprobs(actor, ref, tok)
+    el, ek = oracle.token_logprobs_kl(wl.to_storage(actor), wl.to_storage(ref), tok, rb.RLHF_BF16)
+    assert kl[0] == 0.0
+    assert logp[6] == 0 and kl[6] == 0 and logp[7] == 0 and kl[7] == 0
+    assert np.isinf(ek[2]) and np.isinf(kl[2]) and kl[2] > 0
+    fin = [0, 1, 3, 4, 5, 6, 7]
+    assert np.isfinite(kl[fin]).all() and np.isfinite(logp).all()
+    assert np.abs(logp - el).max() <= LOGP_TOL
+    assert np.abs(kl[fin] - ek[fin]).max() <= LOGP_TOL * max(1.0, np.abs(ek[fin]).max() / 100)
+    assert abs(logp[5]) <= 1e-6 and abs(logp[3]) <= 1e-3
+
+
+@pytest.mark.parametrize("cfg_index", [2, 3, 5])
+def test_logprobs_full_size_sampled_rows(gu, oracle, cfg_index):
+    """The benchmark's launch at the full shape; the oracle checks the first and
+    last rows and a seeded sample in between."""
+    cfg = wl.config(cfg_index)
+    n = cfg.n_positions
+    _say(f"logprob full cfg{cfg_index}: N={n} V={cfg.vocab} bytes={2 * n * cfg.vocab * 2 / 1e9:.1f} GB")
+    actor, ref = wl.logits(cfg, device=gu.DEV)
+    tok = wl.tokens(cfg)
+    logp, kl = gu.run_logprobs(actor, ref, tok)
+    assert np.isfinite(logp).all() and np.isfinite(kl).all()
+    assert (logp < 0).all() and (kl > -1e-5).all()
+    rng = np.random.default_rng(cfg.seed)
+    rows = np.unique(np.concatenate([np.arange(64), np.arange(n - 64, n), rng.integers(0, n, 128)]))
+    idx = torch.from_numpy(rows).to(gu.DEV)
+    el, ek = oracle.token_logprobs_kl(wl.to_storage(actor[idx]), wl.to_storage(ref[idx]), tok[rows],
+                                      wl.DTYPE_CODE[cfg.logits_dtype])
+    _say(f"  {rows.size} rows: max-abs err logp {np.abs(logp[rows] - el).max():.3e} "
+         f"kl {np.abs(kl[rows] - ek).max():.3e}")
+    assert np.abs(logp[rows] - el).max() <= LOGP_TOL
+    assert np.abs(kl[rows] - ek).max() <= LOGP_TOL
