@@ -20,6 +20,15 @@
 //            are wave-uniform (v_readlane), so the lane owns two output dims
 //            and needs no cross-lane reduction for P*V.
 // All accumulation is fp32; probabilities stay fp32.
+//
+// Grouped-query heads (several query heads per KV head) turn both products into
+// small matrix products, and those go to the matrix cores (attn_split_gqa_kernel):
+// the same 1 KiB K load is the A operand of a 16x16x32 MFMA whose B operand is
+// the group's q rows, giving S^T[slot][q head]; its result registers, after the
+// softmax, are already laid out as the B operand of the 16x16x16 MFMAs that
+// multiply V^T (A operand, straight from the V block's 8-byte granules) into
+// O^T[dim][q head].  Probabilities are fed as a high and a low 16-bit part so
+// that the product keeps fp32-level accuracy.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -49,7 +58,10 @@ SplitPlan make_plan(const rlhf_attn_params &p)
     SplitPlan plan;
     const int cap = p.max_pages_per_seq * kPage;
     plan.max_len = (p.max_seq_len > 0 && p.max_seq_len < cap) ? p.max_seq_len : cap;
-    const int64_t units = (int64_t)p.batch * p.n_q_heads;
+    const int group = p.n_q_heads / p.n_kv_heads;
+    // one item covers one query head, or up to 16 heads of a group on the MFMA path
+    const int64_t units = group == 1 ? (int64_t)p.batch * p.n_q_heads
+                                     : (int64_t)p.batch * p.n_kv_heads * ((group + 15) / 16);
     const int max_pages = (plan.max_len + kPage - 1) / kPage;
     int ppi = 32;
     while (ppi > 4 && units * ((max_pages + ppi - 1) / ppi) < 8192)
@@ -223,6 +235,229 @@ __global__ __launch_bounds__(kSplitThreads) void attn_split_kernel(
     }
 }
 
+// ---- grouped-query variant on the matrix cores --------------------------------
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8_t;
+typedef __attribute__((ext_vector_type(4))) short s16x4_t;
+typedef __attribute__((ext_vector_type(4))) _Float16 f16x4_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+
+// D[16x16] += A[16x32] * B[32x16]; lane l supplies row (A) / column (B) l%16 and
+// the 8 contraction entries of group l/16; it receives D[4*(l/16)+j][l%16].
+template <int DT>
+__device__ __forceinline__ f32x4_t mfma_k32(const uint4 &a, const uint4 &b, f32x4_t c)
+{
+    if constexpr (DT == RLHF_BF16)
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a),
+                                                       __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, a),
+                                                      __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
+}
+
+// Same with 16 contraction entries, 4 per lane (entries 4*(l/16) .. +3).
+template <int DT>
+__device__ __forceinline__ f32x4_t mfma_k16(const uint2 &a, const uint2 &b, f32x4_t c)
+{
+    if constexpr (DT == RLHF_BF16)
+        return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4_t, a),
+                                                         __builtin_bit_cast(s16x4_t, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(f16x4_t, a),
+                                                     __builtin_bit_cast(f16x4_t, b), c, 0, 0, 0);
+}
+
+// Splits two fp32 probabilities into packed 16-bit high parts and packed 16-bit
+// remainders: p ~= hi + lo with relative error about 2^-16 (bf16) or better.
+template <int DT>
+__device__ __forceinline__ void split_pair(float p0, float p1, uint32_t &hi, uint32_t &lo)
+{
+    if constexpr (DT == RLHF_BF16) {
+        const uint32_t u0 = __float_as_uint(p0), u1 = __float_as_uint(p1);
+        hi = (u0 >> 16) | (u1 & 0xffff0000u);
+        const float r0 = p0 - __uint_as_float(u0 & 0xffff0000u);  // exact
+        const float r1 = p1 - __uint_as_float(u1 & 0xffff0000u);
+        lo = (__float_as_uint(r0) >> 16) | (__float_as_uint(r1) & 0xffff0000u);
+    } else {
+        const _Float16 h0 = (_Float16)p0, h1 = (_Float16)p1;
+        const _Float16 l0 = (_Float16)(p0 - (float)h0), l1 = (_Float16)(p1 - (float)h1);
+        hi = (uint32_t)__builtin_bit_cast(uint16_t, h0) | ((uint32_t)__builtin_bit_cast(uint16_t, h1) << 16);
+        lo = (uint32_t)__builtin_bit_cast(uint16_t, l0) | ((uint32_t)__builtin_bit_cast(uint16_t, l1) << 16);
+    }
+}
+
+// One workgroup per (sequence, KV head, block of <= 16 query heads of its group,
+// chunk).  Lane l = (group g = l/16, column c = l%16): c is a slot when the lane
+// feeds K, a query head when it feeds q or holds scores and outputs.
+template <int DT, int D>
+__global__ __launch_bounds__(kSplitThreads) void attn_split_gqa_kernel(
+    const uint16_t *__restrict__ q, const uint16_t *__restrict__ k_arena,
+    const uint16_t *__restrict__ v_arena, const int32_t *__restrict__ page_table,
+    const int32_t *__restrict__ seq_lens, float *__restrict__ partials, int n_q_heads, int n_kv_heads,
+    int mpps, int pages_per_item, int n_chunks, int max_len, float scale_log2)
+{
+    constexpr int NL = D / 32;      // 16-byte loads per lane for one K (or V) block
+    constexpr int LDS_ROW = D + 1;  // padded against bank conflicts
+    __shared__ float s_m[kSplitWaves][16], s_l[kSplitWaves][16];
+    __shared__ float s_o[kSplitWaves][16][LDS_ROW];
+
+    const int group = n_q_heads / n_kv_heads;
+    const int n_qb = (group + 15) >> 4;
+    int idx = blockIdx.x;
+    const int chunk = idx % n_chunks;
+    idx /= n_chunks;
+    const int qb = idx % n_qb;
+    idx /= n_qb;
+    const int hkv = idx % n_kv_heads;
+    const int b = idx / n_kv_heads;
+    const int L = min(seq_lens[b], max_len);
+    const int first_page = chunk * pages_per_item;
+    if (first_page * kPage >= L)
+        return;
+    const int end_page = min(first_page + pages_per_item, (L + kPage - 1) / kPage);
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int g = lane >> 4, c = lane & 15;
+    const int head0 = hkv * group + qb * 16;     // first query head of this block
+    const int n_heads = min(16, group - qb * 16);
+
+    // q as the B operand: column c = head, contraction entries = dims 8*(4i+g) .. +8
+    uint4 qr[NL];
+#pragma unroll
+    for (int i = 0; i < NL; ++i) {
+        qr[i] = make_uint4(0, 0, 0, 0);
+        if (c < n_heads)
+            qr[i] = load16(q + ((int64_t)b * n_q_heads + head0 + c) * D + (4 * i + g) * 8);
+    }
+
+    const int32_t *table = page_table + (int64_t)b * mpps;
+    const int64_t head_off = (int64_t)hkv * (kPage * D);
+    const int64_t page_stride = (int64_t)n_kv_heads * (kPage * D);
+    const int k_lane = lane * 8;                 // K: granule 64*i + lane
+    const int v_lane = (g * D + 2 * c) * 4;      // V: granules (quad g, dims 32*i + 2c, +1)
+
+    float m = -INFINITY, lsum = 0.f;
+    f32x4_t o[NL][2];
+#pragma unroll
+    for (int i = 0; i < NL; ++i)
+        o[i][0] = o[i][1] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+    uint4 kb[NL], vb[NL];
+    int lp = first_page + wave;
+    if (lp < end_page) {
+        const int64_t base = (int64_t)table[lp] * page_stride + head_off;
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+            kb[i] = load16(k_arena + base + k_lane + i * 512);
+            vb[i] = load16(v_arena + base + v_lane + i * 128);
+        }
+    }
+    while (lp < end_page) {
+        const int next = lp + kSplitWaves;
+        uint4 kn[NL], vn[NL];
+        if (next < end_page) {
+            const int64_t base = (int64_t)table[next] * page_stride + head_off;
+#pragma unroll
+            for (int i = 0; i < NL; ++i) {
+                kn[i] = load16(k_arena + base + k_lane + i * 512);
+                vn[i] = load16(v_arena + base + v_lane + i * 128);
+            }
+        }
+        // S^T[slot 4g+j][head c]
+        f32x4_t sc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int i = 0; i < NL; ++i)
+            sc = mfma_k32<DT>(kb[i], qr[i], sc);
+        const int live = L - lp * kPage;
+        float y[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            y[j] = (4 * g + j < live) ? sc[j] * scale_log2 : -INFINITY;
+        float mx = fmaxf(fmaxf(y[0], y[1]), fmaxf(y[2], y[3]));
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));      // finite: slot 0 of the page is live
+        const float m_new = fmaxf(m, mx);
+        const float alpha = fast_exp2(m - m_new);
+        float p[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            p[j] = fast_exp2(y[j] - m_new);
+        lsum = fmaf(lsum, alpha, (p[0] + p[1]) + (p[2] + p[3]));
+        m = m_new;
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+            o[i][0] *= alpha;
+            o[i][1] *= alpha;
+        }
+        uint2 ph, pl;
+        split_pair<DT>(p[0], p[1], ph.x, pl.x);
+        split_pair<DT>(p[2], p[3], ph.y, pl.y);
+        if (live < kPage) {  // blank never-written slots: 0 * NaN must not reach the MFMA
+            const uint32_t m01 = (4 * g + 0 < live ? 0x0000ffffu : 0u) | (4 * g + 1 < live ? 0xffff0000u : 0u);
+            const uint32_t m23 = (4 * g + 2 < live ? 0x0000ffffu : 0u) | (4 * g + 3 < live ? 0xffff0000u : 0u);
+#pragma unroll
+            for (int i = 0; i < NL; ++i) {
+                vb[i].x &= m01;
+                vb[i].y &= m23;
+                vb[i].z &= m01;
+                vb[i].w &= m23;
+            }
+        }
+        // O^T[dim][head] += V^T[dim][slot] * P^T[slot][head]
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+            const uint2 v0 = make_uint2(vb[i].x, vb[i].y);  // dim 32i + 2c
+            const uint2 v1 = make_uint2(vb[i].z, vb[i].w);  // dim 32i + 2c + 1
+            o[i][0] = mfma_k16<DT>(v0, ph, o[i][0]);
+            o[i][0] = mfma_k16<DT>(v0, pl, o[i][0]);
+            o[i][1] = mfma_k16<DT>(v1, ph, o[i][1]);
+            o[i][1] = mfma_k16<DT>(v1, pl, o[i][1]);
+        }
+        lp = next;
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+            kb[i] = kn[i];
+            vb[i] = vn[i];
+        }
+    }
+
+    // wavefront result -> LDS.  o[i][e][j] is row 4g+j of its tile, i.e. dim
+    // 32i + 2(4g+j) + e, for head c.
+    lsum += __shfl_xor(lsum, 16);
+    lsum += __shfl_xor(lsum, 32);
+    if (g == 0) {
+        s_m[wave][c] = m;
+        s_l[wave][c] = lsum;
+    }
+#pragma unroll
+    for (int i = 0; i < NL; ++i)
+#pragma unroll
+        for (int e = 0; e < 2; ++e)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                s_o[wave][c][32 * i + 2 * (4 * g + j) + e] = o[i][e][j];
+    __syncthreads();
+    for (int t = threadIdx.x; t < n_heads * (D + 2); t += kSplitThreads) {
+        const int h = t / (D + 2), d = t - h * (D + 2);
+        float M = s_m[0][h];
+#pragma unroll
+        for (int w = 1; w < kSplitWaves; ++w)
+            M = fmaxf(M, s_m[w][h]);
+        float r;
+        if (d == D) {
+            r = M;
+        } else {
+            r = 0.f;
+#pragma unroll
+            for (int w = 0; w < kSplitWaves; ++w)
+                r = fmaf(d < D ? s_o[w][h][d] : s_l[w][h], fast_exp2(s_m[w][h] - M), r);
+        }
+        const int64_t unit = (int64_t)b * n_q_heads + head0 + h;
+        partials[(unit * n_chunks + chunk) * (D + 2) + d] = r;
+    }
+}
+
 // One wavefront per (sequence, query head): out = sum_c w_c o_c / sum_c w_c l_c,
 // w_c = 2^(m_c - max m).
 template <int ODT, int D>
@@ -304,11 +539,21 @@ int launch(const rlhf_attn_params &p, const SplitPlan &plan, const void *q, cons
     const int64_t items = units * plan.n_chunks;
     if (items > 0x7fffffffLL)
         return fail(RLHF_ERR_INVALID, "too many work items for one launch");
-    hipLaunchKernelGGL((attn_split_kernel<DT, D>), dim3((unsigned)items), dim3(kSplitThreads), 0, s,
-                       (const uint16_t *)q, (const uint16_t *)k_arena, (const uint16_t *)v_arena, page_table,
-                       seq_lens, partials, p.n_q_heads, p.n_kv_heads, p.max_pages_per_seq,
-                       plan.pages_per_item, plan.n_chunks, plan.max_len, scale * kLog2e);
-    RLHF_LAUNCH_CHECK("attn_split_kernel");
+    const int group = p.n_q_heads / p.n_kv_heads;
+    if (group == 1) {
+        hipLaunchKernelGGL((attn_split_kernel<DT, D>), dim3((unsigned)items), dim3(kSplitThreads), 0, s,
+                           (const uint16_t *)q, (const uint16_t *)k_arena, (const uint16_t *)v_arena,
+                           page_table, seq_lens, partials, p.n_q_heads, p.n_kv_heads, p.max_pages_per_seq,
+                           plan.pages_per_item, plan.n_chunks, plan.max_len, scale * kLog2e);
+        RLHF_LAUNCH_CHECK("attn_split_kernel");
+    } else {
+        const int64_t gitems = (int64_t)p.batch * p.n_kv_heads * ((group + 15) / 16) * plan.n_chunks;
+        hipLaunchKernelGGL((attn_split_gqa_kernel<DT, D>), dim3((unsigned)gitems), dim3(kSplitThreads), 0, s,
+                           (const uint16_t *)q, (const uint16_t *)k_arena, (const uint16_t *)v_arena,
+                           page_table, seq_lens, partials, p.n_q_heads, p.n_kv_heads, p.max_pages_per_seq,
+                           plan.pages_per_item, plan.n_chunks, plan.max_len, scale * kLog2e);
+        RLHF_LAUNCH_CHECK("attn_split_gqa_kernel");
+    }
     const dim3 mgrid((unsigned)((units + 3) / 4));
     if (p.out_dtype == RLHF_F32)
         hipLaunchKernelGGL((attn_merge_kernel<RLHF_F32, D>), mgrid, dim3(256), 0, s, partials, seq_lens, out,

@@ -124,6 +124,9 @@ SMALL_ATTN = [
     (5, dict(batch=2, n_q_heads=16, n_kv_heads=2, len_lo=2000, len_hi=4096)),
     (5, dict(batch=3, n_q_heads=8, n_kv_heads=2, head_dim=64, len_lo=1, len_hi=300)),
     (1, dict(batch=3, n_q_heads=6, n_kv_heads=2, head_dim=128, len_lo=1, len_hi=70)),
+    (2, dict(batch=3, n_q_heads=8, n_kv_heads=4, len_lo=100, len_hi=400)),            # group of 2
+    (3, dict(batch=2, n_q_heads=48, n_kv_heads=2, len_lo=30, len_hi=900)),            # group of 24 > 16
+    (1, dict(batch=2, n_q_heads=32, n_kv_heads=2, len_lo=200, len_hi=700)),           # f16, group of 16
 ]
 
 
