@@ -58,6 +58,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=5, help="workload index 1..5 (default: the largest)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run three plain 1 GiB device-to-device copies first (a kernel of known "
+                         "traffic, to scale hardware byte counters in a rocprofv3 --pmc run)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU; --gpus above 1 is not supported "
@@ -76,6 +79,13 @@ def main():
     torch.cuda.set_device(0)
     cfg = wl.config(args.config)
     K, W = args.steps, args.warmup
+    if args.calibrate_copy:
+        src = torch.full((1 << 30,), 7, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     P = wl.PAGE_TOKENS
     eb = 2
     lb = 4 if cfg.logits_dtype == "f32" else 2

@@ -2,33 +2,43 @@
 //
 // In the paper's PPO stage the actor generates its responses one token at a
 // time (Section 2.1); each step reads every cached key and value of every
-// sequence once, which makes the step a pure HBM stream.  The token range of a
-// sequence is cut into chunks of a whole number of pages; one workgroup handles
-// one (sequence, query head, chunk) item with an online softmax and writes an
-// un-normalised partial (o, m, l); a second kernel merges the partials of a
-// (sequence, head) with the usual log-sum-exp weights.  Chunks are defined on
-// logical token positions only, so results do not depend on which physical
-// pages a sequence happens to own.
+// sequence once, which makes the step a pure HBM stream.  The work is laid out
+// on one axis of "page steps": sequence after sequence, KV head after KV head,
+// logical page after logical page.  That axis is cut into equal contiguous
+// ranges, one per wavefront, for exactly as many wavefronts as the chip holds
+// at once.  A wavefront streams the pages of its range with an online softmax,
+// and whenever its range leaves a (sequence, head) unit -- or ends -- it writes
+// that unit's un-normalised partial (o, m, l).  A second kernel merges the
+// partials of each (sequence, query head) with log-sum-exp weights.  Every
+// wavefront gets the same number of pages whatever the mix of cache lengths,
+// pays its start-up latency once per call instead of once per chunk, and never
+// synchronises with another wavefront.  Ranges are defined on logical positions
+// only, so results do not depend on which physical pages a sequence owns.
 //
-// Data path of the split kernel (one wavefront works on one page at a time):
-//   K block  [dim/8][16 slots][8 dims]: the wavefront's i-th 16-byte-per-lane
-//            load hands lane l the dims 8*(4i + l/16) .. +8 of slot l%16.  Each
-//            lane dots them with the matching slice of q (v_dot2), and two
-//            cross-row adds finish the 16 scores of the page.
-//   V block  [4 slot-quads][dim][4 slots]: the i-th load hands lane l two
-//            adjacent dims for four consecutive slots; the four probabilities
-//            are wave-uniform (v_readlane), so the lane owns two output dims
-//            and needs no cross-lane reduction for P*V.
-// All accumulation is fp32; probabilities stay fp32.
+// Partial slots need no bookkeeping: along the axis both the wavefront index w
+// and the unit index u only grow, and each new segment raises w + u by at least
+// one, so segment (w, u) simply owns slot w + u.
 //
-// Grouped-query heads (several query heads per KV head) turn both products into
-// small matrix products, and those go to the matrix cores (attn_split_gqa_kernel):
-// the same 1 KiB K load is the A operand of a 16x16x32 MFMA whose B operand is
-// the group's q rows, giving S^T[slot][q head]; its result registers, after the
-// softmax, are already laid out as the B operand of the 16x16x16 MFMAs that
-// multiply V^T (A operand, straight from the V block's 8-byte granules) into
-// O^T[dim][q head].  Probabilities are fed as a high and a low 16-bit part so
-// that the product keeps fp32-level accuracy.
+// Data path (a wavefront works on one page-head block at a time, the next
+// block's loads already in flight):
+//   K block  [dim/8][16 slots][8 dims]: the i-th 16-byte-per-lane load hands
+//            lane l the dims 8*(4i + l/16) .. +8 of slot l%16.
+//   V block  [4 slot-quads][dim][4 slots] in 8-byte granules.
+//   One query head per KV head (attn_stream_kernel): each lane dots its K
+//   granules with the matching slice of q (v_dot2) and two cross-row adds
+//   finish the page's 16 scores; the V loads hand a lane two adjacent dims for
+//   four consecutive slots whose probabilities are wave-uniform (v_readlane),
+//   so a lane owns two output dims and P*V needs no cross-lane reduction.
+//   Probabilities stay fp32.
+//   Grouped-query heads (attn_stream_gqa_kernel) make both products small
+//   matrix products, and those go to the matrix cores: the same 1 KiB K load is
+//   the A operand of a 16x16x32 MFMA whose B operand is the group's q rows,
+//   giving S^T[slot][q head]; its result registers, after the softmax, are
+//   already laid out as the B operand of the 16x16x16 MFMAs that multiply V^T
+//   (A operand, straight from the V block's granules) into O^T[dim][q head].
+//   Probabilities are fed as a high and a low 16-bit part so that the product
+//   keeps fp32-level accuracy.
+// All accumulation is fp32.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -41,86 +51,214 @@ namespace rlhf {
 namespace {
 
 constexpr int kPage = RLHF_PAGE_TOKENS;
-constexpr int kSplitThreads = 256;
-constexpr int kSplitWaves = 4;
+constexpr int kThreads = 256;
+constexpr int kWgWaves = 4;
+constexpr int kMaxBatch = 8192;  // the per-workgroup page-count prefix lives in LDS
 
-struct SplitPlan {
-    int pages_per_item;  // chunk length in pages
-    int n_chunks;        // chunks that cover max_len
-    int max_len;
+// Wavefronts launched = compute units x wavefronts each kernel keeps resident
+// per unit (set by its register use); sizes the partial buffer.  The launch
+// uses fewer if the device reports less room.
+constexpr int kComputeUnits = 256;
+constexpr int kWavesPerCuMha = 32;
+constexpr int kWavesPerCuGqa = 12;
+
+struct Shape {
+    int batch, n_q_heads, n_kv_heads, group;
+    int heads_per_unit;   // query heads one unit covers: 1, or up to 16 of a group
+    int units_per_seq;    // units per sequence
+    int mpps, max_len;
+    int n_waves;          // upper bound used for sizing
 };
 
-// Chunk length: the longest of 64/32/16/8/4 pages that still yields a few
-// thousand items (several per workgroup slot of the 256 compute units).  Every
-// item pays a fixed start-up and merge cost of a few microseconds of its slot,
-// so long chunks win as long as the slots stay evenly loaded; short caches fall
-// back to 4 pages (one per wavefront).  Depends on the call's parameters only.
-SplitPlan make_plan(const rlhf_attn_params &p)
+Shape make_shape(const rlhf_attn_params &p)
 {
-    SplitPlan plan;
+    Shape s;
+    s.batch = p.batch;
+    s.n_q_heads = p.n_q_heads;
+    s.n_kv_heads = p.n_kv_heads;
+    s.group = p.n_q_heads / p.n_kv_heads;
+    s.heads_per_unit = std::min(s.group, 16);
+    s.units_per_seq = s.group == 1 ? p.n_q_heads : p.n_kv_heads * ((s.group + 15) / 16);
+    s.mpps = p.max_pages_per_seq;
     const int cap = p.max_pages_per_seq * kPage;
-    plan.max_len = (p.max_seq_len > 0 && p.max_seq_len < cap) ? p.max_seq_len : cap;
-    const int group = p.n_q_heads / p.n_kv_heads;
-    // one item covers one query head, or up to 16 heads of a group on the MFMA path
-    const int64_t units = group == 1 ? (int64_t)p.batch * p.n_q_heads
-                                     : (int64_t)p.batch * p.n_kv_heads * ((group + 15) / 16);
-    const int max_pages = (plan.max_len + kPage - 1) / kPage;
-    int ppi = 64;
-    while (ppi > 4 && units * ((max_pages + ppi - 1) / ppi) < 3072)
-        ppi >>= 1;
-    plan.pages_per_item = ppi;
-    plan.n_chunks = std::max(1, (max_pages + ppi - 1) / ppi);
-    return plan;
+    s.max_len = (p.max_seq_len > 0 && p.max_seq_len < cap) ? p.max_seq_len : cap;
+    s.n_waves = kComputeUnits * (s.group == 1 ? kWavesPerCuMha : kWavesPerCuGqa);
+    return s;
 }
 
+// Workspace: [0, prefix_bytes) page-count prefix P[0..batch] (int32), then the
+// partial rows of D+2 floats.
+size_t prefix_bytes(const Shape &s)
+{
+    return (((size_t)s.batch + 2) * sizeof(int32_t) + 255) / 256 * 256;
+}
+size_t partial_rows(const Shape &s)
+{
+    return ((size_t)s.n_waves + (size_t)s.batch * s.units_per_seq) * s.heads_per_unit;
+}
+
+// ---- position on the page-step axis -----------------------------------------
+// Step s of the axis is page `page` of unit (b, h): s = U * P[b] + h * np + page,
+// where U = units per sequence, P = exclusive prefix of pages per sequence and
+// np = pages of sequence b.
+struct Cursor {
+    int b, h, page, np, len;
+};
+
+__device__ __forceinline__ int pages_of(int len, int max_len)
+{
+    return (min(max(len, 0), max_len) + kPage - 1) / kPage;
+}
+
+// Builds P[0..batch] in LDS from the device lengths; every thread of the
+// workgroup must call it.  Returns the total number of pages.
+__device__ __forceinline__ int build_prefix(const int32_t *__restrict__ seq_lens, int batch, int max_len,
+                                            int *s_prefix, int *s_scan)
+{
+    const int tid = threadIdx.x;
+    const int per = (batch + kThreads - 1) / kThreads;
+    const int lo = min(tid * per, batch), hi = min(lo + per, batch);
+    int sum = 0;
+    for (int b = lo; b < hi; ++b)
+        sum += pages_of(seq_lens[b], max_len);
+    s_scan[tid] = sum;
+    __syncthreads();
+    // exclusive scan of the 256 segment sums by one wavefront, four per lane
+    if (tid < 64) {
+        const int a0 = s_scan[4 * tid], a1 = s_scan[4 * tid + 1], a2 = s_scan[4 * tid + 2],
+                  a3 = s_scan[4 * tid + 3];
+        const int t = a0 + a1 + a2 + a3;
+        int incl = t;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int o = __shfl_up(incl, d);
+            if (tid >= d)
+                incl += o;
+        }
+        const int excl = incl - t;
+        s_scan[4 * tid] = excl;
+        s_scan[4 * tid + 1] = excl + a0;
+        s_scan[4 * tid + 2] = excl + a0 + a1;
+        s_scan[4 * tid + 3] = excl + a0 + a1 + a2;
+        if (tid == 63)
+            s_prefix[batch] = incl;
+    }
+    __syncthreads();
+    int run = s_scan[tid];
+    for (int b = lo; b < hi; ++b) {
+        s_prefix[b] = run;
+        run += pages_of(seq_lens[b], max_len);
+    }
+    __syncthreads();
+    return s_prefix[batch];
+}
+
+// Cursor for step s (0 <= s < units * total pages).
+__device__ __forceinline__ Cursor locate(int64_t s, const int *s_prefix, const int32_t *__restrict__ seq_lens,
+                                         int batch, int units, int max_len)
+{
+    // largest b with units * P[b] <= s: sequences without pages share their
+    // successor's P and are skipped by taking the largest
+    int lo = 0, hi = batch - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if ((int64_t)units * s_prefix[mid] <= s)
+            lo = mid;
+        else
+            hi = mid - 1;
+    }
+    Cursor c;
+    c.b = lo;
+    c.np = s_prefix[lo + 1] - s_prefix[lo];
+    const int r = (int)(s - (int64_t)units * s_prefix[lo]);
+    c.h = r / c.np;
+    c.page = r - c.h * c.np;
+    c.len = min(seq_lens[lo], max_len);
+    return c;
+}
+
+// Cursor of the next step.  Only called when a next step exists inside the
+// wavefront's range, so a following sequence with pages exists when needed.
+__device__ __forceinline__ Cursor advance(Cursor c, const int *s_prefix, const int32_t *__restrict__ seq_lens,
+                                          int batch, int units, int max_len)
+{
+    if (++c.page < c.np)
+        return c;
+    c.page = 0;
+    if (++c.h < units)
+        return c;
+    c.h = 0;
+    do {
+        ++c.b;
+    } while (c.b < batch - 1 && s_prefix[c.b + 1] == s_prefix[c.b]);
+    c.np = s_prefix[c.b + 1] - s_prefix[c.b];
+    c.len = min(seq_lens[c.b], max_len);
+    return c;
+}
+
+__device__ __forceinline__ Cursor uniform(Cursor c)
+{
+    c.b = __builtin_amdgcn_readfirstlane(c.b);
+    c.h = __builtin_amdgcn_readfirstlane(c.h);
+    c.page = __builtin_amdgcn_readfirstlane(c.page);
+    c.np = __builtin_amdgcn_readfirstlane(c.np);
+    c.len = __builtin_amdgcn_readfirstlane(c.len);
+    return c;
+}
+
+// Range w of n owns steps [w*S/n, (w+1)*S/n); with n <= S no range is empty.
+__device__ __forceinline__ int64_t range_begin(int64_t w, int64_t total, int n)
+{
+    return w * total / n;
+}
+
+// ---- one query head per KV head: vector ALU ----------------------------------
 template <int DT, int D>
-__global__ __launch_bounds__(kSplitThreads) void attn_split_kernel(
+__global__ __launch_bounds__(kThreads) void attn_stream_kernel(
     const uint16_t *__restrict__ q, const uint16_t *__restrict__ k_arena,
     const uint16_t *__restrict__ v_arena, const int32_t *__restrict__ page_table,
-    const int32_t *__restrict__ seq_lens, float *__restrict__ partials, int n_q_heads, int n_kv_heads,
-    int mpps, int pages_per_item, int n_chunks, int max_len, float scale_log2)
+    const int32_t *__restrict__ seq_lens, int32_t *__restrict__ prefix_out, float *__restrict__ partials,
+    int batch, int n_heads, int mpps, int max_len, int n_waves, float scale_log2)
 {
     constexpr int NL = D / 32;  // 16-byte loads per lane for one K (or V) block
-    __shared__ float s_m[kSplitWaves], s_l[kSplitWaves];
-    __shared__ float s_o[kSplitWaves][D];
-
-    const int chunk = blockIdx.x % n_chunks;
-    const int unit = blockIdx.x / n_chunks;  // b * Hq + hq
-    const int b = unit / n_q_heads;
-    const int hq = unit - b * n_q_heads;
-    const int hkv = hq / (n_q_heads / n_kv_heads);
-    const int L = min(seq_lens[b], max_len);
-    const int first_page = chunk * pages_per_item;
-    if (first_page * kPage >= L)
-        return;
-    const int end_page = min(first_page + pages_per_item, (L + kPage - 1) / kPage);
+    extern __shared__ int s_dyn[];
+    int *s_prefix = s_dyn;            // [batch + 1]
+    int *s_scan = s_dyn + batch + 1;  // [256]
+    const int total_pages = build_prefix(seq_lens, batch, max_len, s_prefix, s_scan);
+    if (blockIdx.x == 0)
+        for (int i = threadIdx.x; i <= batch; i += kThreads)
+            prefix_out[i] = s_prefix[i];
 
     const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int w = __builtin_amdgcn_readfirstlane(blockIdx.x * kWgWaves + (threadIdx.x >> 6));
+    const int64_t total = (int64_t)total_pages * n_heads;
+    const int n_ranges = (int)min((int64_t)n_waves, total);  // never more wavefronts than steps
+    if (w >= n_ranges)
+        return;
+    const int64_t s0 = range_begin(w, total, n_ranges), s1 = range_begin(w + 1, total, n_ranges);
     const int slot = lane & 15;
+    const int64_t page_stride = (int64_t)n_heads * (kPage * D);
 
-    // q slices matching the K loads
+    Cursor cur = uniform(locate(s0, s_prefix, seq_lens, batch, n_heads, max_len));
     uint4 qr[NL];
-    const uint16_t *qrow = q + (int64_t)unit * D;
+    auto load_q = [&](const Cursor &c) {
+        const uint16_t *qrow = q + ((int64_t)c.b * n_heads + c.h) * D;
 #pragma unroll
-    for (int i = 0; i < NL; ++i)
-        qr[i] = load16(qrow + (4 * i + (lane >> 4)) * 8);
-
-    const int32_t *table = page_table + (int64_t)b * mpps;
-    const int64_t head_off = (int64_t)hkv * (kPage * D);
-    const int64_t page_stride = (int64_t)n_kv_heads * (kPage * D);
-
-    float m = -INFINITY, lsum = 0.f, acc0 = 0.f, acc1 = 0.f;
-
-    auto load_page = [&](int page_index, uint4(&kd)[NL], uint4(&vd)[NL]) {
-        const int64_t base = (int64_t)table[page_index] * page_stride + head_off + lane * 8;
+        for (int i = 0; i < NL; ++i)
+            qr[i] = load16(qrow + (4 * i + (lane >> 4)) * 8);
+    };
+    auto load_page = [&](const Cursor &c, uint4(&kd)[NL], uint4(&vd)[NL]) {
+        const int page = page_table[(int64_t)c.b * mpps + c.page];
+        const int64_t base = (int64_t)page * page_stride + (int64_t)c.h * (kPage * D) + lane * 8;
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
             kd[i] = load16(k_arena + base + i * 512);
             vd[i] = load16(v_arena + base + i * 512);
         }
     };
-    auto process_page = [&](int lp, const uint4(&kb)[NL], uint4(&vb)[NL]) {
+
+    float m = -INFINITY, lsum = 0.f, acc0 = 0.f, acc1 = 0.f;
+    auto process_page = [&](const Cursor &c, const uint4(&kb)[NL], uint4(&vb)[NL]) {
         // scores of the page's 16 slots
         float part = 0.f;
 #pragma unroll
@@ -132,8 +270,9 @@ __global__ __launch_bounds__(kSplitThreads) void attn_split_kernel(
         }
         part += __shfl_xor(part, 16);
         part += __shfl_xor(part, 32);
-        const float y = (lp * kPage + slot < L) ? part * scale_log2 : -INFINITY;
-        const float m_new = fmaxf(m, row16_max(y));  // finite: the page holds >= 1 live slot
+        const int live = c.len - c.page * kPage;  // >= 1
+        const float y = (slot < live) ? part * scale_log2 : -INFINITY;
+        const float m_new = fmaxf(m, row16_max(y));  // finite: slot 0 is live
         const float alpha = fast_exp2(m - m_new);
         const float p = fast_exp2(y - m_new);
         lsum = fmaf(lsum, alpha, p);
@@ -143,20 +282,20 @@ __global__ __launch_bounds__(kSplitThreads) void attn_split_kernel(
         // Slots past the sequence's end have probability 0, but whatever bits sit
         // there (never written, possibly NaN) must not reach 0 * v: blank them.
         // Only the last page of a sequence can be partial; the branch is uniform.
-        const int live = L - lp * kPage;
         if (live < kPage) {
 #pragma unroll
             for (int i = 0; i < NL; ++i) {
-                const int s0 = 4 * ((D == 128) ? i : 2 * i + (lane >> 5));
-                const uint32_t m01 = (s0 + 0 < live ? 0x0000ffffu : 0u) | (s0 + 1 < live ? 0xffff0000u : 0u);
-                const uint32_t m23 = (s0 + 2 < live ? 0x0000ffffu : 0u) | (s0 + 3 < live ? 0xffff0000u : 0u);
+                const int q0 = 4 * ((D == 128) ? i : 2 * i + (lane >> 5));
+                const uint32_t m01 = (q0 + 0 < live ? 0x0000ffffu : 0u) | (q0 + 1 < live ? 0xffff0000u : 0u);
+                const uint32_t m23 = (q0 + 2 < live ? 0x0000ffffu : 0u) | (q0 + 3 < live ? 0xffff0000u : 0u);
                 vb[i].x &= m01;
                 vb[i].y &= m23;
                 vb[i].z &= m01;
                 vb[i].w &= m23;
             }
         }
-        // P * V
+        // P * V: load i holds slot quad i (D = 128) or quads 2i, 2i+1 in the two
+        // halves of the wavefront (D = 64); lane l owns dims 2l, 2l+1 (mod D)
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
             float pj[4];
@@ -180,66 +319,48 @@ __global__ __launch_bounds__(kSplitThreads) void attn_split_kernel(
             acc1 = fmaf(pj[3], unpack_hi<DT>(vb[i].w), acc1);
         }
     };
-
-    // The wavefront's pages, one ahead: the next page's loads are in flight while
-    // the current one is consumed.  The last page is peeled off so that the
-    // prefetch inside the loop is unconditional (a conditional one would force the
-    // wait counters to cover both cases and serialise load and compute).
-    int lp = first_page + wave;
-    if (lp < end_page) {
-        uint4 kb[NL], vb[NL];
-        load_page(lp, kb, vb);
-        for (int next = lp + kSplitWaves; next < end_page; next += kSplitWaves) {
-            uint4 kn[NL], vn[NL];
-            load_page(next, kn, vn);
-            process_page(lp, kb, vb);
-#pragma unroll
-            for (int i = 0; i < NL; ++i) {
-                kb[i] = kn[i];
-                vb[i] = vn[i];
-            }
-            lp = next;
+    // Writes the finished segment of unit (b, h) to slot w + unit and clears the state.
+    auto flush = [&](const Cursor &c) {
+        const float l_all = row16_sum(lsum);
+        float o0 = acc0, o1 = acc1;
+        if constexpr (D == 64) {  // lanes l and l+32 hold the two halves of the slot quads
+            o0 += __shfl_xor(o0, 32);
+            o1 += __shfl_xor(o1, 32);
         }
-        process_page(lp, kb, vb);
-    }
+        float *dst = partials + ((int64_t)w + (int64_t)c.b * n_heads + c.h) * (D + 2);
+        if (lane < D / 2)
+            *(float2 *)(dst + 2 * lane) = make_float2(o0, o1);
+        if (lane == 0)
+            *(float2 *)(dst + D) = make_float2(m, l_all);
+        m = -INFINITY;
+        lsum = acc0 = acc1 = 0.f;
+    };
 
-    // wavefront result -> LDS
-    const float l_wave = row16_sum(lsum);
-    if constexpr (D == 64) {  // lanes l and l+32 hold the two halves of the slot quads
-        acc0 += __shfl_xor(acc0, 32);
-        acc1 += __shfl_xor(acc1, 32);
-    }
-    if (lane == 0) {
-        s_m[wave] = m;
-        s_l[wave] = l_wave;
-    }
-    if (lane < D / 2) {
-        s_o[wave][2 * lane] = acc0;
-        s_o[wave][2 * lane + 1] = acc1;
-    }
-    __syncthreads();
-    if (threadIdx.x < D + 2) {
-        float M = s_m[0];
-#pragma unroll
-        for (int w = 1; w < kSplitWaves; ++w)
-            M = fmaxf(M, s_m[w]);
-        float *dst = partials + ((int64_t)unit * n_chunks + chunk) * (D + 2);
-        if (threadIdx.x < D) {
-            float o = 0.f;
-#pragma unroll
-            for (int w = 0; w < kSplitWaves; ++w)
-                o = fmaf(s_o[w][threadIdx.x], fast_exp2(s_m[w] - M), o);
-            dst[threadIdx.x] = o;
-        } else if (threadIdx.x == D) {
-            dst[D] = M;
-        } else {
-            float l = 0.f;
-#pragma unroll
-            for (int w = 0; w < kSplitWaves; ++w)
-                l = fmaf(s_l[w], fast_exp2(s_m[w] - M), l);
-            dst[D + 1] = l;
+    // One page ahead: the next block's loads are in flight while the current one
+    // is consumed.  The last step is peeled off so that the prefetch inside the
+    // loop is unconditional (a conditional one would force the wait counters to
+    // cover both cases and serialise load and compute).
+    uint4 kb[NL], vb[NL];
+    load_q(cur);
+    load_page(cur, kb, vb);
+    for (int64_t s = s0 + 1; s < s1; ++s) {
+        const Cursor nxt = uniform(advance(cur, s_prefix, seq_lens, batch, n_heads, max_len));
+        uint4 kn[NL], vn[NL];
+        load_page(nxt, kn, vn);
+        process_page(cur, kb, vb);
+        if (nxt.page == 0) {  // the range moves on to another unit
+            flush(cur);
+            load_q(nxt);
         }
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+            kb[i] = kn[i];
+            vb[i] = vn[i];
+        }
+        cur = nxt;
     }
+    process_page(cur, kb, vb);
+    flush(cur);
 }
 
 // ---- grouped-query variant on the matrix cores --------------------------------
@@ -293,56 +414,66 @@ __device__ __forceinline__ void split_pair(float p0, float p1, uint32_t &hi, uin
     }
 }
 
-// One workgroup per (sequence, KV head, block of <= 16 query heads of its group,
-// chunk).  Lane l = (group g = l/16, column c = l%16): c is a slot when the lane
-// feeds K, a query head when it feeds q or holds scores and outputs.
+// A unit is (sequence, KV head, block of <= 16 query heads of its group): unit
+// index h of a sequence = kv head * blocks per group + block.  Lane l = (group
+// g = l/16, column c = l%16): c is a slot when the lane feeds K, a query head
+// when it feeds q or holds scores and outputs.
 template <int DT, int D>
-__global__ __launch_bounds__(kSplitThreads) void attn_split_gqa_kernel(
+__global__ __launch_bounds__(kThreads) void attn_stream_gqa_kernel(
     const uint16_t *__restrict__ q, const uint16_t *__restrict__ k_arena,
     const uint16_t *__restrict__ v_arena, const int32_t *__restrict__ page_table,
-    const int32_t *__restrict__ seq_lens, float *__restrict__ partials, int n_q_heads, int n_kv_heads,
-    int mpps, int pages_per_item, int n_chunks, int max_len, float scale_log2)
+    const int32_t *__restrict__ seq_lens, int32_t *__restrict__ prefix_out, float *__restrict__ partials,
+    int batch, int n_q_heads, int n_kv_heads, int mpps, int max_len, int n_waves, float scale_log2)
 {
-    constexpr int NL = D / 32;      // 16-byte loads per lane for one K (or V) block
-    constexpr int LDS_ROW = D + 1;  // padded against bank conflicts
-    __shared__ float s_m[kSplitWaves][16], s_l[kSplitWaves][16];
-    __shared__ float s_o[kSplitWaves][16][LDS_ROW];
+    constexpr int NL = D / 32;
+    extern __shared__ int s_dyn[];
+    int *s_prefix = s_dyn;
+    int *s_scan = s_dyn + batch + 1;
+    const int total_pages = build_prefix(seq_lens, batch, max_len, s_prefix, s_scan);
+    if (blockIdx.x == 0)
+        for (int i = threadIdx.x; i <= batch; i += kThreads)
+            prefix_out[i] = s_prefix[i];
 
     const int group = n_q_heads / n_kv_heads;
     const int n_qb = (group + 15) >> 4;
-    int idx = blockIdx.x;
-    const int chunk = idx % n_chunks;
-    idx /= n_chunks;
-    const int qb = idx % n_qb;
-    idx /= n_qb;
-    const int hkv = idx % n_kv_heads;
-    const int b = idx / n_kv_heads;
-    const int L = min(seq_lens[b], max_len);
-    const int first_page = chunk * pages_per_item;
-    if (first_page * kPage >= L)
-        return;
-    const int end_page = min(first_page + pages_per_item, (L + kPage - 1) / kPage);
-
+    const int units = n_kv_heads * n_qb;  // per sequence
+    const int rows_per_unit = min(group, 16);
     const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int w = __builtin_amdgcn_readfirstlane(blockIdx.x * kWgWaves + (threadIdx.x >> 6));
+    const int64_t total = (int64_t)total_pages * units;
+    const int n_ranges = (int)min((int64_t)n_waves, total);  // never more wavefronts than steps
+    if (w >= n_ranges)
+        return;
+    const int64_t s0 = range_begin(w, total, n_ranges), s1 = range_begin(w + 1, total, n_ranges);
     const int g = lane >> 4, c = lane & 15;
-    const int head0 = hkv * group + qb * 16;     // first query head of this block
-    const int n_heads = min(16, group - qb * 16);
+    const int64_t page_stride = (int64_t)n_kv_heads * (kPage * D);
+    const int k_lane = lane * 8;             // K: granule 64*i + lane
+    const int v_lane = (g * D + 2 * c) * 4;  // V: granules (quad g, dims 32*i + 2c, +1)
 
+    Cursor cur = uniform(locate(s0, s_prefix, seq_lens, batch, units, max_len));
     // q as the B operand: column c = head, contraction entries = dims 8*(4i+g) .. +8
     uint4 qr[NL];
+    int n_heads_here = 0;
+    auto load_q = [&](const Cursor &cu) {
+        const int hkv = cu.h / n_qb, qb = cu.h - hkv * n_qb;
+        const int head0 = hkv * group + qb * 16;
+        n_heads_here = min(16, group - qb * 16);
 #pragma unroll
-    for (int i = 0; i < NL; ++i) {
-        qr[i] = make_uint4(0, 0, 0, 0);
-        if (c < n_heads)
-            qr[i] = load16(q + ((int64_t)b * n_q_heads + head0 + c) * D + (4 * i + g) * 8);
-    }
-
-    const int32_t *table = page_table + (int64_t)b * mpps;
-    const int64_t head_off = (int64_t)hkv * (kPage * D);
-    const int64_t page_stride = (int64_t)n_kv_heads * (kPage * D);
-    const int k_lane = lane * 8;                 // K: granule 64*i + lane
-    const int v_lane = (g * D + 2 * c) * 4;      // V: granules (quad g, dims 32*i + 2c, +1)
+        for (int i = 0; i < NL; ++i) {
+            qr[i] = make_uint4(0, 0, 0, 0);
+            if (c < n_heads_here)
+                qr[i] = load16(q + ((int64_t)cu.b * n_q_heads + head0 + c) * D + (4 * i + g) * 8);
+        }
+    };
+    auto load_page = [&](const Cursor &cu, uint4(&kd)[NL], uint4(&vd)[NL]) {
+        const int page = page_table[(int64_t)cu.b * mpps + cu.page];
+        const int64_t base = (int64_t)page * page_stride + (int64_t)(cu.h / n_qb) * (kPage * D);
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+            kd[i] = load16(k_arena + base + k_lane + i * 512);
+            vd[i] = load16(v_arena + base + v_lane + i * 128);
+        }
+    };
 
     float m = -INFINITY, lsum = 0.f;
     f32x4_t o[NL][2];
@@ -350,28 +481,20 @@ __global__ __launch_bounds__(kSplitThreads) void attn_split_gqa_kernel(
     for (int i = 0; i < NL; ++i)
         o[i][0] = o[i][1] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-    auto load_page = [&](int page_index, uint4(&kd)[NL], uint4(&vd)[NL]) {
-        const int64_t base = (int64_t)table[page_index] * page_stride + head_off;
-#pragma unroll
-        for (int i = 0; i < NL; ++i) {
-            kd[i] = load16(k_arena + base + k_lane + i * 512);
-            vd[i] = load16(v_arena + base + v_lane + i * 128);
-        }
-    };
-    auto process_page = [&](int lp, const uint4(&kb)[NL], uint4(&vb)[NL]) {
+    auto process_page = [&](const Cursor &cu, const uint4(&kb)[NL], uint4(&vb)[NL]) {
         // S^T[slot 4g+j][head c]
         f32x4_t sc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int i = 0; i < NL; ++i)
             sc = mfma_k32<DT>(kb[i], qr[i], sc);
-        const int live = L - lp * kPage;
+        const int live = cu.len - cu.page * kPage;
         float y[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j)
             y[j] = (4 * g + j < live) ? sc[j] * scale_log2 : -INFINITY;
         float mx = fmaxf(fmaxf(y[0], y[1]), fmaxf(y[2], y[3]));
         mx = fmaxf(mx, __shfl_xor(mx, 16));
-        mx = fmaxf(mx, __shfl_xor(mx, 32));      // finite: slot 0 of the page is live
+        mx = fmaxf(mx, __shfl_xor(mx, 32));  // finite: slot 0 of the page is live
         const float m_new = fmaxf(m, mx);
         const float alpha = fast_exp2(m - m_new);
         float p[4];
@@ -410,99 +533,142 @@ __global__ __launch_bounds__(kSplitThreads) void attn_split_gqa_kernel(
             o[i][1] = mfma_k16<DT>(v1, pl, o[i][1]);
         }
     };
-
-    // one page ahead, last page peeled (see attn_split_kernel)
-    int lp = first_page + wave;
-    if (lp < end_page) {
-        uint4 kb[NL], vb[NL];
-        load_page(lp, kb, vb);
-        for (int next = lp + kSplitWaves; next < end_page; next += kSplitWaves) {
-            uint4 kn[NL], vn[NL];
-            load_page(next, kn, vn);
-            process_page(lp, kb, vb);
+    // o[i][e][j] is row 4g+j of its tile, i.e. dim 32i + 2(4g+j) + e, for head c.
+    auto flush = [&](const Cursor &cu) {
+        float l_all = lsum + __shfl_xor(lsum, 16);
+        l_all += __shfl_xor(l_all, 32);
+        if (c < n_heads_here) {
+            float *dst = partials +
+                         (((int64_t)w + (int64_t)cu.b * units + cu.h) * rows_per_unit + c) * (D + 2);
 #pragma unroll
-            for (int i = 0; i < NL; ++i) {
-                kb[i] = kn[i];
-                vb[i] = vn[i];
-            }
-            lp = next;
+            for (int i = 0; i < NL; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    *(float2 *)(dst + 32 * i + 2 * (4 * g + j)) = make_float2(o[i][0][j], o[i][1][j]);
+            if (g == 0)
+                *(float2 *)(dst + D) = make_float2(m, l_all);
         }
-        process_page(lp, kb, vb);
-    }
+        m = -INFINITY;
+        lsum = 0.f;
+#pragma unroll
+        for (int i = 0; i < NL; ++i)
+            o[i][0] = o[i][1] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    };
 
-    // wavefront result -> LDS.  o[i][e][j] is row 4g+j of its tile, i.e. dim
-    // 32i + 2(4g+j) + e, for head c.
-    lsum += __shfl_xor(lsum, 16);
-    lsum += __shfl_xor(lsum, 32);
-    if (g == 0) {
-        s_m[wave][c] = m;
-        s_l[wave][c] = lsum;
-    }
-#pragma unroll
-    for (int i = 0; i < NL; ++i)
-#pragma unroll
-        for (int e = 0; e < 2; ++e)
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                s_o[wave][c][32 * i + 2 * (4 * g + j) + e] = o[i][e][j];
-    __syncthreads();
-    for (int t = threadIdx.x; t < n_heads * (D + 2); t += kSplitThreads) {
-        const int h = t / (D + 2), d = t - h * (D + 2);
-        float M = s_m[0][h];
-#pragma unroll
-        for (int w = 1; w < kSplitWaves; ++w)
-            M = fmaxf(M, s_m[w][h]);
-        float r;
-        if (d == D) {
-            r = M;
-        } else {
-            r = 0.f;
-#pragma unroll
-            for (int w = 0; w < kSplitWaves; ++w)
-                r = fmaf(d < D ? s_o[w][h][d] : s_l[w][h], fast_exp2(s_m[w][h] - M), r);
+    // one page ahead, last step peeled (see attn_stream_kernel)
+    uint4 kb[NL], vb[NL];
+    load_q(cur);
+    load_page(cur, kb, vb);
+    for (int64_t s = s0 + 1; s < s1; ++s) {
+        const Cursor nxt = uniform(advance(cur, s_prefix, seq_lens, batch, units, max_len));
+        uint4 kn[NL], vn[NL];
+        load_page(nxt, kn, vn);
+        process_page(cur, kb, vb);
+        if (nxt.page == 0) {
+            flush(cur);
+            load_q(nxt);
         }
-        const int64_t unit = (int64_t)b * n_q_heads + head0 + h;
-        partials[(unit * n_chunks + chunk) * (D + 2) + d] = r;
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+            kb[i] = kn[i];
+            vb[i] = vn[i];
+        }
+        cur = nxt;
     }
+    process_page(cur, kb, vb);
+    flush(cur);
 }
 
-// One wavefront per (sequence, query head): out = sum_c w_c o_c / sum_c w_c l_c,
-// w_c = 2^(m_c - max m).
+// One wavefront per (sequence, query head): finds the wavefronts whose ranges
+// touched the head's unit, then out = sum_w e_w o_w / sum_w e_w l_w with
+// e_w = 2^(m_w - max m).
 template <int ODT, int D>
 __global__ __launch_bounds__(256) void attn_merge_kernel(
-    const float *__restrict__ partials, const int32_t *__restrict__ seq_lens, void *__restrict__ out,
-    int n_units, int n_q_heads, int pages_per_item, int n_chunks, int max_len)
+    const float *__restrict__ partials, const int32_t *__restrict__ prefix, void *__restrict__ out,
+    int batch, int n_q_heads, int n_kv_heads, int n_waves)
 {
     const int lane = threadIdx.x & 63;
-    const int unit = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (unit >= n_units)
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);  // b * Hq + hq
+    if (row >= (int64_t)batch * n_q_heads)
         return;
-    const int b = unit / n_q_heads;
-    const int L = min(seq_lens[b], max_len);
-    const int chunk_tokens = pages_per_item * kPage;
-    const int n = (L + chunk_tokens - 1) / chunk_tokens;
-    const float *src = partials + (int64_t)unit * n_chunks * (D + 2);
-    float M = -INFINITY;
-    for (int c = 0; c < n; ++c)
-        M = fmaxf(M, src[c * (D + 2) + D]);
+    const int b = (int)(row / n_q_heads);
+    const int hq = (int)(row - (int64_t)b * n_q_heads);
+    const int group = n_q_heads / n_kv_heads;
+    int units, h, col, rows_per_unit;
+    if (group == 1) {
+        units = n_q_heads;
+        h = hq;
+        col = 0;
+        rows_per_unit = 1;
+    } else {
+        const int n_qb = (group + 15) >> 4;
+        const int hkv = hq / group, qi = hq - hkv * group;
+        units = n_kv_heads * n_qb;
+        h = hkv * n_qb + (qi >> 4);
+        col = qi & 15;
+        rows_per_unit = min(group, 16);
+    }
+    const int np = prefix[b + 1] - prefix[b];
+    const int64_t total = (int64_t)prefix[batch] * units;
     constexpr int PER = D / 64;
     float o[PER], l = 0.f;
 #pragma unroll
     for (int k = 0; k < PER; ++k)
         o[k] = 0.f;
-    for (int c = 0; c < n; ++c) {
-        const float *pc = src + c * (D + 2);
-        const float w = fast_exp2(pc[D] - M);
-        l = fmaf(pc[D + 1], w, l);
+    if (np > 0) {
+        const int64_t first = (int64_t)units * prefix[b] + (int64_t)h * np, last = first + np - 1;
+        // wavefront that owns step s: the largest w with w*total/n <= s, where n is
+        // the number of ranges the stream kernel used (every range is non-empty)
+        const int64_t n = min((int64_t)n_waves, total);
+        const int64_t w_first = ((first + 1) * n + total - 1) / total - 1;
+        const int64_t w_last = ((last + 1) * n + total - 1) / total - 1;
+        const int count = (int)(w_last - w_first + 1);
+        const int64_t row_stride = (int64_t)rows_per_unit * (D + 2);
+        const float *base = partials + ((w_first + (int64_t)b * units + h) * rows_per_unit + col) * (D + 2);
+        // pass 1: the largest exponent; lanes take one segment each
+        float M = -INFINITY;
+        for (int i = lane; i < count; i += 64)
+            M = fmaxf(M, base[i * row_stride + D]);
+        M = wave_max(M);
+        // pass 2: weights per lane, then the weighted rows with several loads in flight
+        for (int i0 = 0; i0 < count; i0 += 64) {
+            const int i = i0 + lane;
+            float e = 0.f, le = 0.f;
+            if (i < count) {
+                e = fast_exp2(base[i * row_stride + D] - M);
+                le = base[i * row_stride + D + 1] * e;
+            }
+            l += wave_sum(le);
+            const int chunk = min(64, count - i0);
+            int j = 0;
+            for (; j + 4 <= chunk; j += 4) {
+                float v[4][PER], ej[4];
 #pragma unroll
-        for (int k = 0; k < PER; ++k)
-            o[k] = fmaf(pc[lane + 64 * k], w, o[k]);
+                for (int u = 0; u < 4; ++u) {
+                    ej[u] = __shfl(e, j + u);
+#pragma unroll
+                    for (int k = 0; k < PER; ++k)
+                        v[u][k] = base[(int64_t)(i0 + j + u) * row_stride + lane + 64 * k];
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+#pragma unroll
+                    for (int k = 0; k < PER; ++k)
+                        o[k] = fmaf(v[u][k], ej[u], o[k]);
+            }
+            for (; j < chunk; ++j) {
+                const float ej = __shfl(e, j);
+#pragma unroll
+                for (int k = 0; k < PER; ++k)
+                    o[k] = fmaf(base[(int64_t)(i0 + j) * row_stride + lane + 64 * k], ej, o[k]);
+            }
+        }
     }
-    const float inv = n > 0 ? 1.0f / l : 0.f;
+    const float inv = np > 0 ? 1.0f / l : 0.f;
 #pragma unroll
     for (int k = 0; k < PER; ++k) {
-        const float r = n > 0 ? o[k] * inv : 0.f;
-        const int64_t idx = (int64_t)unit * D + lane + 64 * k;
+        const float r = np > 0 ? o[k] * inv : 0.f;
+        const int64_t idx = row * D + lane + 64 * k;
         if constexpr (ODT == RLHF_F32)
             ((float *)out)[idx] = r;
         else
@@ -527,48 +693,64 @@ int check_params(const rlhf_attn_params *p)
         return fail(RLHF_ERR_UNSUPPORTED, "qkv_dtype %d (f16 or bf16)", p->qkv_dtype);
     if (p->out_dtype != p->qkv_dtype && p->out_dtype != RLHF_F32)
         return fail(RLHF_ERR_UNSUPPORTED, "out_dtype must be the qkv dtype or f32");
-    if ((int64_t)p->max_pages_per_seq * kPage > 0x7fffffffLL)
-        return fail(RLHF_ERR_INVALID, "max_pages_per_seq too large");
+    if (p->batch > kMaxBatch)
+        return fail(RLHF_ERR_UNSUPPORTED, "batch %d above %d: split the call", p->batch, kMaxBatch);
+    if ((int64_t)p->max_pages_per_seq * kPage > 0x7fffffffLL ||
+        (int64_t)p->batch * p->max_pages_per_seq > 0x7fffffffLL)
+        return fail(RLHF_ERR_INVALID, "page table too large");
     return RLHF_OK;
 }
 
-size_t workspace_bytes(const rlhf_attn_params &p, const SplitPlan &plan)
+// Wavefronts the device can hold at once for a kernel, capped by the sizing bound.
+template <typename Kernel>
+int resident_waves(Kernel kernel, size_t lds_bytes, int bound, int *out)
 {
-    return (size_t)p.batch * p.n_q_heads * plan.n_chunks * (p.head_dim + 2) * sizeof(float);
+    int dev = 0, cus = 0, blocks = 0;
+    RLHF_HIP_TRY(hipGetDevice(&dev));
+    RLHF_HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+    RLHF_HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, kernel, kThreads, lds_bytes));
+    const int64_t waves = (int64_t)cus * std::max(blocks, 1) * kWgWaves;
+    *out = (int)std::min<int64_t>(waves, bound);
+    return RLHF_OK;
 }
 
 template <int DT, int D>
-int launch(const rlhf_attn_params &p, const SplitPlan &plan, const void *q, const void *k_arena,
+int launch(const rlhf_attn_params &p, const Shape &sh, const void *q, const void *k_arena,
            const void *v_arena, const int32_t *page_table, const int32_t *seq_lens, void *out,
-           float *partials, hipStream_t s)
+           void *workspace, hipStream_t s)
 {
     const float scale = p.softmax_scale != 0.f ? p.softmax_scale : 1.0f / sqrtf((float)D);
-    const int64_t units = (int64_t)p.batch * p.n_q_heads;
-    const int64_t items = units * plan.n_chunks;
-    if (items > 0x7fffffffLL)
-        return fail(RLHF_ERR_INVALID, "too many work items for one launch");
-    const int group = p.n_q_heads / p.n_kv_heads;
-    if (group == 1) {
-        hipLaunchKernelGGL((attn_split_kernel<DT, D>), dim3((unsigned)items), dim3(kSplitThreads), 0, s,
+    int32_t *prefix = (int32_t *)workspace;
+    float *partials = (float *)((char *)workspace + prefix_bytes(sh));
+    const size_t lds = ((size_t)p.batch + 1 + kThreads) * sizeof(int);
+    int n_waves = 0, rc;
+    if (sh.group == 1) {
+        rc = resident_waves(attn_stream_kernel<DT, D>, lds, sh.n_waves, &n_waves);
+        if (rc != RLHF_OK)
+            return rc;
+        hipLaunchKernelGGL((attn_stream_kernel<DT, D>), dim3(n_waves / kWgWaves), dim3(kThreads), lds, s,
                            (const uint16_t *)q, (const uint16_t *)k_arena, (const uint16_t *)v_arena,
-                           page_table, seq_lens, partials, p.n_q_heads, p.n_kv_heads, p.max_pages_per_seq,
-                           plan.pages_per_item, plan.n_chunks, plan.max_len, scale * kLog2e);
-        RLHF_LAUNCH_CHECK("attn_split_kernel");
+                           page_table, seq_lens, prefix, partials, p.batch, p.n_q_heads, p.max_pages_per_seq,
+                           sh.max_len, n_waves, scale * kLog2e);
+        RLHF_LAUNCH_CHECK("attn_stream_kernel");
     } else {
-        const int64_t gitems = (int64_t)p.batch * p.n_kv_heads * ((group + 15) / 16) * plan.n_chunks;
-        hipLaunchKernelGGL((attn_split_gqa_kernel<DT, D>), dim3((unsigned)gitems), dim3(kSplitThreads), 0, s,
+        rc = resident_waves(attn_stream_gqa_kernel<DT, D>, lds, sh.n_waves, &n_waves);
+        if (rc != RLHF_OK)
+            return rc;
+        hipLaunchKernelGGL((attn_stream_gqa_kernel<DT, D>), dim3(n_waves / kWgWaves), dim3(kThreads), lds, s,
                            (const uint16_t *)q, (const uint16_t *)k_arena, (const uint16_t *)v_arena,
-                           page_table, seq_lens, partials, p.n_q_heads, p.n_kv_heads, p.max_pages_per_seq,
-                           plan.pages_per_item, plan.n_chunks, plan.max_len, scale * kLog2e);
-        RLHF_LAUNCH_CHECK("attn_split_gqa_kernel");
+                           page_table, seq_lens, prefix, partials, p.batch, p.n_q_heads, p.n_kv_heads,
+                           p.max_pages_per_seq, sh.max_len, n_waves, scale * kLog2e);
+        RLHF_LAUNCH_CHECK("attn_stream_gqa_kernel");
     }
-    const dim3 mgrid((unsigned)((units + 3) / 4));
+    const int64_t rows = (int64_t)p.batch * p.n_q_heads;
+    const dim3 mgrid((unsigned)((rows + 3) / 4));
     if (p.out_dtype == RLHF_F32)
-        hipLaunchKernelGGL((attn_merge_kernel<RLHF_F32, D>), mgrid, dim3(256), 0, s, partials, seq_lens, out,
-                           (int)units, p.n_q_heads, plan.pages_per_item, plan.n_chunks, plan.max_len);
+        hipLaunchKernelGGL((attn_merge_kernel<RLHF_F32, D>), mgrid, dim3(256), 0, s, partials, prefix, out,
+                           p.batch, p.n_q_heads, p.n_kv_heads, n_waves);
     else
-        hipLaunchKernelGGL((attn_merge_kernel<DT, D>), mgrid, dim3(256), 0, s, partials, seq_lens, out,
-                           (int)units, p.n_q_heads, plan.pages_per_item, plan.n_chunks, plan.max_len);
+        hipLaunchKernelGGL((attn_merge_kernel<DT, D>), mgrid, dim3(256), 0, s, partials, prefix, out, p.batch,
+                           p.n_q_heads, p.n_kv_heads, n_waves);
     RLHF_LAUNCH_CHECK("attn_merge_kernel");
     return RLHF_OK;
 }
@@ -585,7 +767,8 @@ extern "C" int rlhf_decode_attention_workspace_bytes(const rlhf_attn_params *par
     int rc = check_params(params);
     if (rc != RLHF_OK)
         return rc;
-    *out_bytes = std::max<size_t>(16, workspace_bytes(*params, make_plan(*params)));
+    const Shape sh = make_shape(*params);
+    *out_bytes = prefix_bytes(sh) + partial_rows(sh) * (params->head_dim + 2) * sizeof(float);
     return RLHF_OK;
 }
 
@@ -603,18 +786,17 @@ extern "C" int rlhf_decode_attention(const rlhf_attn_params *params, const void 
         return fail(RLHF_ERR_INVALID, "NULL pointer");
     if (((uintptr_t)q | (uintptr_t)k_arena | (uintptr_t)v_arena | (uintptr_t)out | (uintptr_t)workspace) % 16)
         return fail(RLHF_ERR_INVALID, "q, k_arena, v_arena, out and workspace must be 16-byte aligned");
-    const SplitPlan plan = make_plan(p);
-    const size_t need = workspace_bytes(p, plan);
+    const Shape sh = make_shape(p);
+    const size_t need = prefix_bytes(sh) + partial_rows(sh) * (p.head_dim + 2) * sizeof(float);
     if (workspace_bytes_given < need)
         return fail(RLHF_ERR_INVALID, "workspace holds %zu bytes, %zu needed", workspace_bytes_given, need);
     hipStream_t s = (hipStream_t)stream;
-    float *partials = (float *)workspace;
     if (p.qkv_dtype == RLHF_BF16) {
         if (p.head_dim == 128)
-            return launch<RLHF_BF16, 128>(p, plan, q, k_arena, v_arena, page_table, seq_lens, out, partials, s);
-        return launch<RLHF_BF16, 64>(p, plan, q, k_arena, v_arena, page_table, seq_lens, out, partials, s);
+            return launch<RLHF_BF16, 128>(p, sh, q, k_arena, v_arena, page_table, seq_lens, out, workspace, s);
+        return launch<RLHF_BF16, 64>(p, sh, q, k_arena, v_arena, page_table, seq_lens, out, workspace, s);
     }
     if (p.head_dim == 128)
-        return launch<RLHF_F16, 128>(p, plan, q, k_arena, v_arena, page_table, seq_lens, out, partials, s);
-    return launch<RLHF_F16, 64>(p, plan, q, k_arena, v_arena, page_table, seq_lens, out, partials, s);
+        return launch<RLHF_F16, 128>(p, sh, q, k_arena, v_arena, page_table, seq_lens, out, workspace, s);
+    return launch<RLHF_F16, 64>(p, sh, q, k_arena, v_arena, page_table, seq_lens, out, workspace, s);
 }
