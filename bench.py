@@ -28,6 +28,32 @@ HBM_PEAK_GBPS = 8000.0     # MI355X, HBM3E
 METRIC = "decode-attn HBM GB/s (% of MI355X peak) + logprob/KL tokens/sec, 1 GPU"
 
 
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by a
+# plain 1 GiB copy; see profiles/bench_cfg5_gqa70b_hbm_traffic.txt), valid for workload 5 and
+# only while the kernel sources still hash to the value recorded with them.
+PMC_TRAFFIC = {
+    "logprob_kl": {"sources": ["logprob_kl.hip", "device_ops.h"],
+                   "sha256": "74881942a0a0ba2ce6083f227752f09b957d0284ddd4433724795e97d0fc4a8f",
+                   "bytes": 67249726834 + 9066664},
+    "decode_attn": {"sources": ["attention.hip", "device_ops.h"],
+                    "sha256": "7a4496821e3ef1d9f1f80c7dad9fb17a41be8080552a689ad18a39e7a18f5333",
+                    "bytes": 1605456389 + 12761448 + 13416415 + 2097152},
+}
+
+
+def measured_traffic(name, cfg_index):
+    """Counter-measured HBM bytes per launch, or None when the kernel has changed
+    since the counters were taken (or for another workload)."""
+    import hashlib
+    entry = PMC_TRAFFIC[name]
+    if cfg_index != 5:
+        return None
+    h = hashlib.sha256()
+    for f in entry["sources"]:
+        h.update(open(os.path.join(ROOT, "paper_2410_15651_amd", "csrc", f), "rb").read())
+    return entry["bytes"] if h.hexdigest() == entry["sha256"] else None
+
+
 def log(msg):
     print(msg, file=sys.stderr, flush=True)
 
@@ -197,10 +223,13 @@ def main():
         },
         "roofline": {"kernel": "logprob_kl_kernel", "bound": "hbm", "achieved": round(logp_gbps, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(logp_gbps / HBM_PEAK_GBPS, 4),
-                     "traffic": None},
-        "roofline_decode_attn": {"kernel": "attn_split_kernel+attn_merge_kernel", "bound": "hbm",
+                     "traffic": measured_traffic("logprob_kl", cfg.index)},
+        "roofline_decode_attn": {"kernel": ("attn_stream_kernel" if cfg.n_q_heads == cfg.n_kv_heads
+                                            else "attn_stream_gqa_kernel") + "+attn_merge_kernel",
+                                 "bound": "hbm",
                                  "achieved": round(attn_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                                 "frac": round(attn_gbps / HBM_PEAK_GBPS, 4), "traffic": None},
+                                 "frac": round(attn_gbps / HBM_PEAK_GBPS, 4),
+                                 "traffic": measured_traffic("decode_attn", cfg.index)},
     }
 
     if not args.no_cpu_baseline:
