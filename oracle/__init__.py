@@ -24,25 +24,35 @@ _SRC = os.path.join(_HERE, "rollout_oracle.c")
 _LIB = os.path.join(_HERE, "librollout_oracle.so")
 
 F16, BF16, F32 = 0, 1, 2
-_lib = None
 
 
-def build(force: bool = False) -> str:
+def build(force: bool = False, src: str = _SRC, lib: str = _LIB) -> str:
     """Compile the C oracle (gcc, OpenMP) if it is missing or stale."""
-    if (not force and os.path.exists(_LIB)
-            and os.path.getmtime(_LIB) >= os.path.getmtime(_SRC)):
-        return _LIB
+    if (not force and os.path.exists(lib)
+            and os.path.getmtime(lib) >= os.path.getmtime(src)):
+        return lib
     cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared",
-           "-fno-fast-math", "-Wall", "-Wextra", _SRC, "-o", _LIB, "-lm"]
+           "-fno-fast-math", "-Wall", "-Wextra", src, "-o", lib, "-lm"]
     subprocess.run(cmd, check=True)
-    return _LIB
+    return lib
 
 
-def _load():
-    global _lib
-    if _lib is None:
-        build()
-        lib = ctypes.CDLL(_LIB)
+def _storage(arr: np.ndarray, dtype: int) -> np.ndarray:
+    want = np.float32 if dtype == F32 else np.uint16
+    if arr.dtype != want:
+        raise TypeError(f"dtype code {dtype} needs a {want.__name__} array, got {arr.dtype}")
+    return np.ascontiguousarray(arr)
+
+
+class OracleLib:
+    """The compiled oracle behind numpy wrappers.  The module-level functions use
+    the in-tree build; tests that plant a mistake in a copy of the C source load
+    that copy through this class."""
+
+    F16, BF16, F32 = F16, BF16, F32
+
+    def __init__(self, lib_path: str):
+        lib = ctypes.CDLL(lib_path)
         lib.oracle_num_threads.restype = ctypes.c_int
         lib.oracle_decode_attention.restype = ctypes.c_int
         lib.oracle_decode_attention.argtypes = [
@@ -55,69 +65,84 @@ def _load():
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
             ctypes.c_void_p, ctypes.c_void_p,
             ctypes.c_int64, ctypes.c_int, ctypes.c_int64, ctypes.c_int]
-        _lib = lib
-    return _lib
+        self._lib = lib
+
+    def num_threads(self) -> int:
+        return int(self._lib.oracle_num_threads())
+
+    def decode_attention(self, q, k_pages, v_pages, page_table, seq_lens, dtype, scale=None,
+                         return_weights=False):
+        """q [B,Hq,D], k_pages/v_pages [n_pages,Hkv,P,D] (plain token-major pages),
+        page_table [B,max_pages] int32, seq_lens [B] int32 -> out [B,Hq,D] float64."""
+        q = _storage(q, dtype)
+        k_pages = _storage(k_pages, dtype)
+        v_pages = _storage(v_pages, dtype)
+        B, Hq, D = q.shape
+        n_pages, Hkv, P, D2 = k_pages.shape
+        assert D2 == D and v_pages.shape == k_pages.shape
+        page_table = np.ascontiguousarray(page_table, dtype=np.int32).reshape(B, -1)
+        seq_lens = np.ascontiguousarray(seq_lens, dtype=np.int32)
+        assert seq_lens.shape == (B,)
+        max_pages = page_table.shape[1]
+        used = (seq_lens.astype(np.int64) + P - 1) // P
+        for b in range(B):
+            row = page_table[b, :used[b]]
+            if row.size and (row.min() < 0 or row.max() >= n_pages):
+                raise ValueError("page table entry out of range")
+        if scale is None:
+            scale = 1.0 / np.sqrt(D)
+        out = np.zeros((B, Hq, D), dtype=np.float64)
+        weights = np.zeros((B, Hq, max_pages * P), dtype=np.float64) if return_weights else None
+        rc = self._lib.oracle_decode_attention(
+            q.ctypes.data, k_pages.ctypes.data, v_pages.ctypes.data,
+            page_table.ctypes.data, seq_lens.ctypes.data, out.ctypes.data,
+            weights.ctypes.data if return_weights else None,
+            B, Hq, Hkv, D, P, max_pages, dtype, float(scale))
+        if rc != 0:
+            raise ValueError("oracle_decode_attention rejected its arguments")
+        return (out, weights) if return_weights else out
+
+    def token_logprobs_kl(self, actor, ref, tokens, dtype, vocab=None):
+        """actor/ref [N,stride] rows (first `vocab` columns used), tokens [N] int32
+        -> (logp [N], kl [N]) float64."""
+        actor = _storage(actor, dtype)
+        ref = _storage(ref, dtype)
+        assert actor.shape == ref.shape and actor.ndim == 2
+        N, stride = actor.shape
+        V = stride if vocab is None else int(vocab)
+        tokens = np.ascontiguousarray(tokens, dtype=np.int32)
+        assert tokens.shape == (N,)
+        logp = np.zeros(N, dtype=np.float64)
+        kl = np.zeros(N, dtype=np.float64)
+        rc = self._lib.oracle_token_logprobs_kl(
+            actor.ctypes.data, ref.ctypes.data, tokens.ctypes.data,
+            logp.ctypes.data, kl.ctypes.data, N, V, stride, dtype)
+        if rc != 0:
+            raise ValueError("oracle_token_logprobs_kl rejected its arguments")
+        return logp, kl
+
+
+_default = None
+
+
+def _load() -> OracleLib:
+    global _default
+    if _default is None:
+        _default = OracleLib(build())
+    return _default
 
 
 def num_threads() -> int:
-    return int(_load().oracle_num_threads())
+    return _load().num_threads()
 
 
-def _storage(arr: np.ndarray, dtype: int) -> np.ndarray:
-    want = np.float32 if dtype == F32 else np.uint16
-    if arr.dtype != want:
-        raise TypeError(f"dtype code {dtype} needs a {want.__name__} array, got {arr.dtype}")
-    return np.ascontiguousarray(arr)
+def decode_attention(*args, **kw):
+    return _load().decode_attention(*args, **kw)
 
 
-def decode_attention(q, k_pages, v_pages, page_table, seq_lens, dtype, scale=None,
-                     return_weights=False):
-    """q [B,Hq,D], k_pages/v_pages [n_pages,Hkv,P,D] (plain token-major pages),
-    page_table [B,max_pages] int32, seq_lens [B] int32 -> out [B,Hq,D] float64."""
-    q = _storage(q, dtype)
-    k_pages = _storage(k_pages, dtype)
-    v_pages = _storage(v_pages, dtype)
-    B, Hq, D = q.shape
-    n_pages, Hkv, P, D2 = k_pages.shape
-    assert D2 == D and v_pages.shape == k_pages.shape
-    page_table = np.ascontiguousarray(page_table, dtype=np.int32).reshape(B, -1)
-    seq_lens = np.ascontiguousarray(seq_lens, dtype=np.int32)
-    assert seq_lens.shape == (B,)
-    max_pages = page_table.shape[1]
-    used = (seq_lens.astype(np.int64) + P - 1) // P
-    for b in range(B):
-        row = page_table[b, :used[b]]
-        if row.size and (row.min() < 0 or row.max() >= n_pages):
-            raise ValueError("page table entry out of range")
-    if scale is None:
-        scale = 1.0 / np.sqrt(D)
-    out = np.zeros((B, Hq, D), dtype=np.float64)
-    weights = np.zeros((B, Hq, max_pages * P), dtype=np.float64) if return_weights else None
-    rc = _load().oracle_decode_attention(
-        q.ctypes.data, k_pages.ctypes.data, v_pages.ctypes.data,
-        page_table.ctypes.data, seq_lens.ctypes.data, out.ctypes.data,
-        weights.ctypes.data if return_weights else None,
-        B, Hq, Hkv, D, P, max_pages, dtype, float(scale))
-    if rc != 0:
-        raise ValueError("oracle_decode_attention rejected its arguments")
-    return (out, weights) if return_weights else out
+def token_logprobs_kl(*args, **kw):
+    return _load().token_logprobs_kl(*args, **kw)
 
 
-def token_logprobs_kl(actor, ref, tokens, dtype, vocab=None):
-    """actor/ref [N,stride] rows (first `vocab` columns used), tokens [N] int32
-    -> (logp [N], kl [N]) float64."""
-    actor = _storage(actor, dtype)
-    ref = _storage(ref, dtype)
-    assert actor.shape == ref.shape and actor.ndim == 2
-    N, stride = actor.shape
-    V = stride if vocab is None else int(vocab)
-    tokens = np.ascontiguousarray(tokens, dtype=np.int32)
-    assert tokens.shape == (N,)
-    logp = np.zeros(N, dtype=np.float64)
-    kl = np.zeros(N, dtype=np.float64)
-    rc = _load().oracle_token_logprobs_kl(
-        actor.ctypes.data, ref.ctypes.data, tokens.ctypes.data,
-        logp.ctypes.data, kl.ctypes.data, N, V, stride, dtype)
-    if rc != 0:
-        raise ValueError("oracle_token_logprobs_kl rejected its arguments")
-    return logp, kl
+decode_attention.__doc__ = OracleLib.decode_attention.__doc__
+token_logprobs_kl.__doc__ = OracleLib.token_logprobs_kl.__doc__

@@ -1,0 +1,116 @@
+"""Are the oracle's pins strong enough?  Each case plants one plausible mistake
+in a copy of the oracle's C source (on the CPU, in a temporary directory),
+builds it, and runs the pin tests of test_oracle_attention.py and
+test_oracle_logprob_kl.py against the copy.  Every planted mistake must make at
+least one pin fail; the unmodified source must pass them all."""
+import inspect
+import os
+
+import pytest
+
+import oracle as oracle_pkg
+import test_oracle_attention as pins_attention
+import test_oracle_logprob_kl as pins_logprob
+
+SRC = os.path.join(os.path.dirname(oracle_pkg.__file__), "rollout_oracle.c")
+
+# (name, text to find exactly once or n times, replacement, which pin module exposes it)
+MUTANTS = [
+    ("attention: scale dropped",
+     "                s *= scale;\n                const double w = exp(s - m);",
+     "                const double w = exp(s - m);", "attention"),
+    ("attention: wrong kv head for a query head", "const int hkv = hq / G;", "const int hkv = hq % Hkv;",
+     "attention"),
+    ("attention: slot index off by one", "((size_t)hkv * P + j % P) * D;\n                double s = 0.0;\n"
+     "                for (int d = 0; d < D; ++d)\n                    s += load_elem(q, qbase + d, dtype) * "
+     "load_elem(k_pages, row + d, dtype);\n                s *= scale;\n                const double w",
+     "((size_t)hkv * P + (j + 1) % P) * D;\n                double s = 0.0;\n"
+     "                for (int d = 0; d < D; ++d)\n                    s += load_elem(q, qbase + d, dtype) * "
+     "load_elem(k_pages, row + d, dtype);\n                s *= scale;\n                const double w",
+     "attention"),
+    ("attention: page table ignored",
+     "const size_t page = (size_t)page_table[(size_t)b * max_pages + j / P];\n"
+     "                const size_t row = page * page_elems + ((size_t)hkv * P + j % P) * D;\n"
+     "                double s = 0.0;\n                for (int d = 0; d < D; ++d)\n"
+     "                    s += load_elem(q, qbase + d, dtype) * load_elem(k_pages, row + d, dtype);\n"
+     "                s *= scale;\n                const double w",
+     "const size_t page = (size_t)(j / P) + 0 * (size_t)page_table[(size_t)b * max_pages];\n"
+     "                const size_t row = page * page_elems + ((size_t)hkv * P + j % P) * D;\n"
+     "                double s = 0.0;\n                for (int d = 0; d < D; ++d)\n"
+     "                    s += load_elem(q, qbase + d, dtype) * load_elem(k_pages, row + d, dtype);\n"
+     "                s *= scale;\n                const double w", "attention"),
+    ("attention: weights not normalised", "                o[d] /= denom;", "                o[d] /= 1.0;",
+     "attention"),
+    ("attention: value rows read from K", "o[d] += w * load_elem(v_pages, row + d, dtype);",
+     "o[d] += w * load_elem(k_pages, row + d, dtype);", "attention"),
+    ("attention: exponent sign", "const double w = exp(s - m);", "const double w = exp(m - s);", "attention"),
+    ("attention: query read backwards in the weight pass",
+     "s += load_elem(q, qbase + d, dtype) * load_elem(k_pages, row + d, dtype);\n                s *= scale;\n"
+     "                const double w",
+     "s += load_elem(q, qbase + (D - 1 - d), dtype) * load_elem(k_pages, row + d, dtype);\n"
+     "                s *= scale;\n                const double w", "attention"),
+    ("widening: bfloat16 shift", "uint32_t u = (uint32_t)b << 16;", "uint32_t u = (uint32_t)b << 15;", "both"),
+    ("widening: binary16 exponent bias", "v = ldexp((double)(f | 0x400), e - 25);",
+     "v = ldexp((double)(f | 0x400), e - 24);", "both"),
+    ("widening: binary16 subnormals", "v = ldexp((double)f, -24);", "v = 0.0;", "both"),
+    ("kl: direction swapped", "acc += p * (la - lr);", "acc += exp(lr) * (lr - la);", "logprob"),
+    ("kl: reference not normalised", "const double lr = load_elem(ref, base + v, dtype) - lse_r;",
+     "const double lr = load_elem(ref, base + v, dtype) - lse_a;", "logprob"),
+    ("kl: weights from the reference", "const double p = exp(la);", "const double p = exp(lr);", "logprob"),
+    ("kl: term dropped", "acc += p * (la - lr);", "acc += p * la;", "logprob"),
+    ("logp: gathered at the wrong token", "logp[i] = load_elem(actor, base + (size_t)tok, dtype) - lse_a;",
+     "logp[i] = load_elem(actor, base + (size_t)(tok > 0 ? tok - 1 : 0), dtype) - lse_a;", "logprob"),
+    ("logp: sign", "logp[i] = load_elem(actor, base + (size_t)tok, dtype) - lse_a;",
+     "logp[i] = lse_a - load_elem(actor, base + (size_t)tok, dtype);", "logprob"),
+    ("logp: base-2 logarithm", "const double lse_a = ma + log(sa);", "const double lse_a = ma + log2(sa);",
+     "logprob"),
+    ("logp: maximum not added back", "const double lse_a = ma + log(sa);", "const double lse_a = log(sa);",
+     "logprob"),
+    ("rows: stride ignored", "const size_t base = (size_t)i * (size_t)stride;",
+     "const size_t base = (size_t)i * (size_t)V;", "logprob"),
+    ("padding: not zeroed", "            logp[i] = 0.0;\n            kl[i] = 0.0;\n            continue;",
+     "            logp[i] = -1.0;\n            kl[i] = 0.0;\n            continue;", "logprob"),
+]
+
+
+def _pins(which):
+    mods = {"attention": [pins_attention], "logprob": [pins_logprob],
+            "both": [pins_attention, pins_logprob]}[which]
+    out = []
+    for mod in mods:
+        for name, fn in sorted(vars(mod).items()):
+            if name.startswith("test_") and list(inspect.signature(fn).parameters) == ["oracle"]:
+                out.append(fn)
+    return out
+
+
+def _build_variant(tmp_path, text, tag):
+    src = tmp_path / f"oracle_{tag}.c"
+    src.write_text(text)
+    lib = str(tmp_path / f"liboracle_{tag}.so")
+    oracle_pkg.build(force=True, src=str(src), lib=lib)
+    return oracle_pkg.OracleLib(lib)
+
+
+def _first_failure(lib, pins):
+    for fn in pins:
+        try:
+            fn(lib)
+        except AssertionError as e:
+            return f"{fn.__name__}: {str(e)[:80]}"
+    return None
+
+
+def test_unmodified_copy_passes_every_pin(tmp_path):
+    lib = _build_variant(tmp_path, open(SRC).read(), "clean")
+    assert len(_pins("both")) >= 30
+    assert _first_failure(lib, _pins("both")) is None
+
+
+@pytest.mark.parametrize("name,find,replace,which", MUTANTS, ids=[m[0] for m in MUTANTS])
+def test_planted_mistake_is_caught(tmp_path, name, find, replace, which):
+    text = open(SRC).read()
+    assert text.count(find) >= 1, "mutation pattern no longer matches the oracle source"
+    lib = _build_variant(tmp_path, text.replace(find, replace), "mutant")
+    failure = _first_failure(lib, _pins(which))
+    assert failure is not None, f"no pin noticed: {name}"
