@@ -78,7 +78,7 @@ typedef enum { RLHF_F16 = 0, RLHF_BF16 = 1, RLHF_F32 = 2 } rlhf_dtype;
  * sequence's pages to the tail of the free list in logical order;
  * rlhf_kv_arena_reset restores initial_free_order.  reset is the arena's
  * counterpart of the cache release the paper inserts after each phase
- * (Section 3.3), at the cost of host integer work only.
+ * (Section 3.3), at the cost of host integer work and two small fill kernels.
  * ------------------------------------------------------------------------ */
 
 typedef struct rlhf_kv_arena rlhf_kv_arena; /* opaque, library-owned */
@@ -227,6 +227,35 @@ int rlhf_decode_attention(const rlhf_attn_params *params, const void *q, const v
 int rlhf_token_logprobs_kl(const void *actor_logits, const void *ref_logits, const int32_t *tokens,
                            float *logp_out, float *kl_out, int64_t n_positions, int32_t vocab,
                            int64_t row_stride_elems, int32_t logits_dtype, void *stream);
+
+/* ------------------------------------------------------------------------
+ * The same pass with per-token reward shaping (Section 2.1: the reference
+ * model is there "to prevent reward divergence", the reward model supplies the
+ * sequence return).  Besides logp_out and kl_out, and at no extra HBM traffic:
+ *     ref_logp_out[i] = log softmax(ref[i,:])[tokens[i]]
+ *     reward_out[i]   = -kl_coef * penalty_i + terminal_scores[i]
+ * with penalty_i = kl_out[i] (RLHF_PENALTY_FULL_KL) or the sampled estimate
+ * logp_out[i] - ref_logp_out[i] (RLHF_PENALTY_SAMPLED), whose expectation over
+ * tokens drawn from the actor is kl_out[i].  terminal_scores (dev [n_positions]
+ * or NULL) is what the caller wants added per position: the sequence's score at
+ * its last generated position, 0 elsewhere.  Padded positions get 0 in every
+ * output.  ref_logp_out and reward_out may each be NULL.
+ * ------------------------------------------------------------------------ */
+#define RLHF_PENALTY_FULL_KL 0
+#define RLHF_PENALTY_SAMPLED 1
+
+typedef struct {
+    float *ref_logp_out;          /* dev [n_positions] or NULL */
+    float *reward_out;            /* dev [n_positions] or NULL */
+    const float *terminal_scores; /* dev [n_positions] or NULL */
+    float kl_coef;
+    int32_t penalty;              /* RLHF_PENALTY_FULL_KL or RLHF_PENALTY_SAMPLED */
+} rlhf_reward_shaping;
+
+int rlhf_token_logprobs_kl_rewards(const void *actor_logits, const void *ref_logits, const int32_t *tokens,
+                                   float *logp_out, float *kl_out, int64_t n_positions, int32_t vocab,
+                                   int64_t row_stride_elems, int32_t logits_dtype,
+                                   const rlhf_reward_shaping *shaping, void *stream);
 
 /* Text for the most recent failure on this thread ("" if none). */
 const char *rlhf_last_error_string(void);

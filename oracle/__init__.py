@@ -65,6 +65,11 @@ class OracleLib:
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
             ctypes.c_void_p, ctypes.c_void_p,
             ctypes.c_int64, ctypes.c_int, ctypes.c_int64, ctypes.c_int]
+        lib.oracle_token_rewards.restype = ctypes.c_int
+        lib.oracle_token_rewards.argtypes = [
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_int64, ctypes.c_int, ctypes.c_int64, ctypes.c_int, ctypes.c_double, ctypes.c_int]
         self._lib = lib
 
     def num_threads(self) -> int:
@@ -122,6 +127,28 @@ class OracleLib:
         return logp, kl
 
 
+    def token_rewards(self, actor, ref, tokens, dtype, kl_coef, sampled_penalty, terminal=None,
+                      vocab=None):
+        """-> (ref_logp [N], reward [N]) float64; terminal [N] float64 or None."""
+        actor = _storage(actor, dtype)
+        ref = _storage(ref, dtype)
+        assert actor.shape == ref.shape and actor.ndim == 2
+        N, stride = actor.shape
+        V = stride if vocab is None else int(vocab)
+        tokens = np.ascontiguousarray(tokens, dtype=np.int32)
+        term = None if terminal is None else np.ascontiguousarray(terminal, dtype=np.float64)
+        assert tokens.shape == (N,) and (term is None or term.shape == (N,))
+        ref_logp = np.zeros(N, dtype=np.float64)
+        reward = np.zeros(N, dtype=np.float64)
+        rc = self._lib.oracle_token_rewards(
+            actor.ctypes.data, ref.ctypes.data, tokens.ctypes.data,
+            None if term is None else term.ctypes.data, ref_logp.ctypes.data, reward.ctypes.data,
+            N, V, stride, dtype, float(kl_coef), int(bool(sampled_penalty)))
+        if rc != 0:
+            raise ValueError("oracle_token_rewards rejected its arguments")
+        return ref_logp, reward
+
+
 _default = None
 
 
@@ -142,6 +169,10 @@ def decode_attention(*args, **kw):
 
 def token_logprobs_kl(*args, **kw):
     return _load().token_logprobs_kl(*args, **kw)
+
+
+def token_rewards(*args, **kw):
+    return _load().token_rewards(*args, **kw)
 
 
 decode_attention.__doc__ = OracleLib.decode_attention.__doc__

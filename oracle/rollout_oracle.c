@@ -18,6 +18,8 @@
  *   oracle_token_logprobs_kl  log-softmax of the actor logits gathered at the
  *                             sampled token, and KL(actor || reference) over
  *                             the whole vocabulary
+ *   oracle_token_rewards      the reference model's log-probability of the
+ *                             token and the KL-penalised per-token reward
  *
  * Inputs arrive in their storage precision (IEEE binary16, bfloat16 or
  * binary32) and are widened exactly to double; every sum, exponential and
@@ -194,6 +196,40 @@ int oracle_decode_attention(const void *q, const void *k_pages, const void *v_pa
  * counts as 0 (so an actor logit of -inf never produces 0 * inf).
  * tokens[i] < 0 or >= V marks a padded position: logp = kl = 0 for it.
  */
+/* One row of the definitions above: log p_actor(tok), log p_ref(tok), KL. */
+static void score_row(const void *actor, const void *ref, size_t base, int V, int dtype, int32_t tok,
+                      double *logp_actor, double *logp_ref, double *kl)
+{
+    double ma = -INFINITY, mr = -INFINITY;
+    for (int v = 0; v < V; ++v) {
+        const double a = load_elem(actor, base + v, dtype);
+        const double r = load_elem(ref, base + v, dtype);
+        if (a > ma)
+            ma = a;
+        if (r > mr)
+            mr = r;
+    }
+    double sa = 0.0, sr = 0.0;
+    for (int v = 0; v < V; ++v) {
+        sa += exp(load_elem(actor, base + v, dtype) - ma);
+        sr += exp(load_elem(ref, base + v, dtype) - mr);
+    }
+    const double lse_a = ma + log(sa);
+    const double lse_r = mr + log(sr);
+
+    double acc = 0.0;
+    for (int v = 0; v < V; ++v) {
+        const double la = load_elem(actor, base + v, dtype) - lse_a; /* log p_v */
+        const double lr = load_elem(ref, base + v, dtype) - lse_r;   /* log q_v */
+        const double p = exp(la);
+        if (p > 0.0)
+            acc += p * (la - lr);
+    }
+    *logp_actor = load_elem(actor, base + (size_t)tok, dtype) - lse_a;
+    *logp_ref = load_elem(ref, base + (size_t)tok, dtype) - lse_r;
+    *kl = acc;
+}
+
 int oracle_token_logprobs_kl(const void *actor, const void *ref, const int32_t *tokens,
                              double *logp, double *kl,
                              int64_t N, int V, int64_t stride, int dtype)
@@ -214,34 +250,47 @@ int oracle_token_logprobs_kl(const void *actor, const void *ref, const int32_t *
             continue;
         }
         const size_t base = (size_t)i * (size_t)stride;
+        double unused;
+        score_row(actor, ref, base, V, dtype, tok, &logp[i], &unused, &kl[i]);
+    }
+    return 0;
+}
 
-        double ma = -INFINITY, mr = -INFINITY;
-        for (int v = 0; v < V; ++v) {
-            const double a = load_elem(actor, base + v, dtype);
-            const double r = load_elem(ref, base + v, dtype);
-            if (a > ma)
-                ma = a;
-            if (r > mr)
-                mr = r;
-        }
-        double sa = 0.0, sr = 0.0;
-        for (int v = 0; v < V; ++v) {
-            sa += exp(load_elem(actor, base + v, dtype) - ma);
-            sr += exp(load_elem(ref, base + v, dtype) - mr);
-        }
-        const double lse_a = ma + log(sa);
-        const double lse_r = mr + log(sr);
+/*
+ * Per-token reward shaping on top of the same row quantities (Section 2.1: the
+ * reference model keeps the reward from diverging; the reward model's score is
+ * the sequence return).  For row i with sampled token tok:
+ *   ref_logp = r_tok - lse_r
+ *   penalty  = KL(actor || ref) of the row            if sampled_penalty == 0
+ *            = log p_actor(tok) - log p_ref(tok)      if sampled_penalty != 0
+ *   reward   = -kl_coef * penalty + terminal[i]       (terminal may be NULL = 0)
+ * Padded positions (tok outside [0, V)) get 0 in both outputs.
+ */
+int oracle_token_rewards(const void *actor, const void *ref, const int32_t *tokens,
+                         const double *terminal, double *ref_logp, double *reward,
+                         int64_t N, int V, int64_t stride, int dtype,
+                         double kl_coef, int sampled_penalty)
+{
+    if (!actor || !ref || !tokens || !ref_logp || !reward || N < 0 || V <= 0)
+        return -1;
+    if (stride == 0)
+        stride = V;
+    if (stride < V)
+        return -1;
 
-        double acc = 0.0;
-        for (int v = 0; v < V; ++v) {
-            const double la = load_elem(actor, base + v, dtype) - lse_a; /* log p_v */
-            const double lr = load_elem(ref, base + v, dtype) - lse_r;   /* log q_v */
-            const double p = exp(la);
-            if (p > 0.0)
-                acc += p * (la - lr);
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < N; ++i) {
+        const int32_t tok = tokens[i];
+        if (tok < 0 || tok >= V) {
+            ref_logp[i] = 0.0;
+            reward[i] = 0.0;
+            continue;
         }
-        logp[i] = load_elem(actor, base + (size_t)tok, dtype) - lse_a;
-        kl[i] = acc;
+        double lpa, lpr, kl;
+        score_row(actor, ref, (size_t)i * (size_t)stride, V, dtype, tok, &lpa, &lpr, &kl);
+        const double penalty = sampled_penalty ? lpa - lpr : kl;
+        ref_logp[i] = lpr;
+        reward[i] = -kl_coef * penalty + (terminal ? terminal[i] : 0.0);
     }
     return 0;
 }

@@ -18,6 +18,7 @@ RLHF_OK, RLHF_ERR_INVALID, RLHF_ERR_OOM, RLHF_ERR_DEVICE, RLHF_ERR_UNSUPPORTED =
 RLHF_F16, RLHF_BF16, RLHF_F32 = 0, 1, 2
 RLHF_PAGE_TOKENS = 16
 RLHF_ARENA_HOST_ONLY = 1
+RLHF_PENALTY_FULL_KL, RLHF_PENALTY_SAMPLED = 0, 1
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "librlhf_rollout.so")
 
@@ -26,6 +27,7 @@ EXPORTS = [
     "rlhf_kv_arena_append", "rlhf_kv_arena_free_seq", "rlhf_kv_arena_reset", "rlhf_kv_arena_stats",
     "rlhf_kv_arena_views", "rlhf_kv_arena_host_state", "rlhf_kv_arena_gather",
     "rlhf_decode_attention_workspace_bytes", "rlhf_decode_attention", "rlhf_token_logprobs_kl",
+    "rlhf_token_logprobs_kl_rewards",
     "rlhf_last_error_string", "rlhf_version",
 ]
 
@@ -64,6 +66,13 @@ class AttnParams(ctypes.Structure):
     ]
 
 
+class RewardShaping(ctypes.Structure):
+    _fields_ = [
+        ("ref_logp_out", ctypes.c_void_p), ("reward_out", ctypes.c_void_p),
+        ("terminal_scores", ctypes.c_void_p), ("kl_coef", ctypes.c_float), ("penalty", ctypes.c_int32),
+    ]
+
+
 _lib = None
 
 
@@ -91,6 +100,8 @@ def lib() -> ctypes.CDLL:
         L.rlhf_decode_attention_workspace_bytes.argtypes = [P(AttnParams), P(sz)]
         L.rlhf_decode_attention.argtypes = [P(AttnParams), vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.rlhf_token_logprobs_kl.argtypes = [vp, vp, vp, vp, vp, i64, i32, i64, i32, vp]
+        L.rlhf_token_logprobs_kl_rewards.argtypes = [vp, vp, vp, vp, vp, i64, i32, i64, i32,
+                                                     P(RewardShaping), vp]
         L.rlhf_last_error_string.restype = ctypes.c_char_p
         L.rlhf_last_error_string.argtypes = []
         L.rlhf_version.argtypes = []
@@ -255,6 +266,24 @@ def rlhf_token_logprobs_kl(actor_logits, ref_logits, tokens, logp_out, kl_out, n
     _check(lib().rlhf_token_logprobs_kl(_ptr(actor_logits), _ptr(ref_logits), _ptr(tokens), _ptr(logp_out),
                                         _ptr(kl_out), n_positions, vocab, row_stride_elems, logits_dtype,
                                         _stream(stream)))
+
+
+def rlhf_token_logprobs_kl_rewards(actor_logits, ref_logits, tokens, logp_out, kl_out, kl_coef,
+                                   penalty=RLHF_PENALTY_FULL_KL, ref_logp_out=None, reward_out=None,
+                                   terminal_scores=None, n_positions=None, vocab=None, row_stride_elems=0,
+                                   logits_dtype=None, stream=None) -> None:
+    if n_positions is None:
+        n_positions = actor_logits.shape[0]
+    if vocab is None:
+        vocab = actor_logits.shape[1]
+        row_stride_elems = actor_logits.stride(0)
+    if logits_dtype is None:
+        logits_dtype = dtype_code(actor_logits.dtype)
+    sh = RewardShaping(_ptr(ref_logp_out), _ptr(reward_out), _ptr(terminal_scores), kl_coef, penalty)
+    _check(lib().rlhf_token_logprobs_kl_rewards(_ptr(actor_logits), _ptr(ref_logits), _ptr(tokens),
+                                                _ptr(logp_out), _ptr(kl_out), n_positions, vocab,
+                                                row_stride_elems, logits_dtype, ctypes.byref(sh),
+                                                _stream(stream)))
 
 
 def rlhf_last_error_string() -> str:

@@ -140,12 +140,22 @@ __device__ __forceinline__ float block_sum(float v, float *lds)
     return r;
 }
 
+// Optional per-token reward shaping done by the lane that writes the row's
+// results (all pointers may be null).
+struct Shaping {
+    float *ref_logp_out;
+    float *reward_out;
+    const float *terminal;
+    float kl_coef;
+    int sampled;
+};
+
 // VEC: rows start 16-byte aligned and are read with 128-bit loads; otherwise
 // every lane reads single elements.
 template <int DT, bool VEC>
 __global__ __launch_bounds__(kThreads) void logprob_kl_kernel(
     const void *__restrict__ actor, const void *__restrict__ ref, const int32_t *__restrict__ tokens,
-    float *__restrict__ logp_out, float *__restrict__ kl_out, int vocab, int64_t stride)
+    float *__restrict__ logp_out, float *__restrict__ kl_out, int vocab, int64_t stride, Shaping sh)
 {
     __shared__ float lds[kWaves];
     const int64_t row = blockIdx.x;
@@ -155,6 +165,10 @@ __global__ __launch_bounds__(kThreads) void logprob_kl_kernel(
         if (tid == 0) {
             logp_out[row] = 0.f;
             kl_out[row] = 0.f;
+            if (sh.ref_logp_out)
+                sh.ref_logp_out[row] = 0.f;
+            if (sh.reward_out)
+                sh.reward_out[row] = 0.f;
         }
         return;
     }
@@ -164,9 +178,14 @@ __global__ __launch_bounds__(kThreads) void logprob_kl_kernel(
     const char *rrow = (const char *)ref + row * stride * EB;
 
     // issue the gather of the sampled token's logit before the long stream
-    float a_tok = 0.f;
-    if (tid == 0)
+    float a_tok = 0.f, r_tok = 0.f, terminal = 0.f;
+    if (tid == 0) {
         a_tok = load_scalar<DT>(arow, tok);
+        if (sh.ref_logp_out || sh.reward_out)
+            r_tok = load_scalar<DT>(rrow, tok);
+        if (sh.reward_out && sh.terminal)
+            terminal = sh.terminal[row];
+    }
 
     RowSums st;
     if constexpr (VEC) {
@@ -224,22 +243,30 @@ __global__ __launch_bounds__(kThreads) void logprob_kl_kernel(
         const float la = log2f(sa), lr = log2f(sr);
         const float lse_a = (a_ref2 + la) * kLn2;
         const float diff2 = (r_ref2 - a_ref2) + (lr - la);
+        const float kl = t / sa + diff2 * kLn2;
         logp_out[row] = a_tok - lse_a;
-        kl_out[row] = t / sa + diff2 * kLn2;
+        kl_out[row] = kl;
+        if (sh.ref_logp_out)
+            sh.ref_logp_out[row] = r_tok - (r_ref2 + lr) * kLn2;
+        if (sh.reward_out) {
+            // sampled estimate logp_a(tok) - logp_r(tok) = (a_tok - r_tok) + (lse_r - lse_a)
+            const float penalty = sh.sampled ? (a_tok - r_tok) + diff2 * kLn2 : kl;
+            sh.reward_out[row] = fmaf(-sh.kl_coef, penalty, terminal);
+        }
     }
 }
 
 template <int DT>
 int launch(const void *actor, const void *ref, const int32_t *tokens, float *logp, float *kl,
-           int64_t n, int vocab, int64_t stride, bool vec, hipStream_t s)
+           int64_t n, int vocab, int64_t stride, bool vec, const Shaping &sh, hipStream_t s)
 {
     const dim3 grid((unsigned)n), block(kThreads);
     if (vec)
         hipLaunchKernelGGL((logprob_kl_kernel<DT, true>), grid, block, 0, s, actor, ref, tokens, logp,
-                           kl, vocab, stride);
+                           kl, vocab, stride, sh);
     else
         hipLaunchKernelGGL((logprob_kl_kernel<DT, false>), grid, block, 0, s, actor, ref, tokens, logp,
-                           kl, vocab, stride);
+                           kl, vocab, stride, sh);
     RLHF_LAUNCH_CHECK("logprob_kl_kernel");
     return RLHF_OK;
 }
@@ -247,10 +274,10 @@ int launch(const void *actor, const void *ref, const int32_t *tokens, float *log
 }  // namespace
 }  // namespace rlhf
 
-extern "C" int rlhf_token_logprobs_kl(const void *actor_logits, const void *ref_logits,
-                                      const int32_t *tokens, float *logp_out, float *kl_out,
-                                      int64_t n_positions, int32_t vocab, int64_t row_stride_elems,
-                                      int32_t logits_dtype, void *stream)
+static int logprobs_kl_impl(const void *actor_logits, const void *ref_logits, const int32_t *tokens,
+                            float *logp_out, float *kl_out, int64_t n_positions, int32_t vocab,
+                            int64_t row_stride_elems, int32_t logits_dtype, const rlhf::Shaping &sh,
+                            void *stream)
 {
     using namespace rlhf;
     if (n_positions < 0 || vocab <= 0)
@@ -276,12 +303,38 @@ extern "C" int rlhf_token_logprobs_kl(const void *actor_logits, const void *ref_
     switch (logits_dtype) {
     case RLHF_F16:
         return launch<RLHF_F16>(actor_logits, ref_logits, tokens, logp_out, kl_out, n_positions, vocab,
-                                row_stride_elems, vec, s);
+                                row_stride_elems, vec, sh, s);
     case RLHF_BF16:
         return launch<RLHF_BF16>(actor_logits, ref_logits, tokens, logp_out, kl_out, n_positions, vocab,
-                                 row_stride_elems, vec, s);
+                                 row_stride_elems, vec, sh, s);
     default:
         return launch<RLHF_F32>(actor_logits, ref_logits, tokens, logp_out, kl_out, n_positions, vocab,
-                                row_stride_elems, vec, s);
+                                row_stride_elems, vec, sh, s);
     }
+}
+
+extern "C" int rlhf_token_logprobs_kl(const void *actor_logits, const void *ref_logits,
+                                      const int32_t *tokens, float *logp_out, float *kl_out,
+                                      int64_t n_positions, int32_t vocab, int64_t row_stride_elems,
+                                      int32_t logits_dtype, void *stream)
+{
+    const rlhf::Shaping none = {nullptr, nullptr, nullptr, 0.f, 0};
+    return logprobs_kl_impl(actor_logits, ref_logits, tokens, logp_out, kl_out, n_positions, vocab,
+                            row_stride_elems, logits_dtype, none, stream);
+}
+
+extern "C" int rlhf_token_logprobs_kl_rewards(const void *actor_logits, const void *ref_logits,
+                                              const int32_t *tokens, float *logp_out, float *kl_out,
+                                              int64_t n_positions, int32_t vocab, int64_t row_stride_elems,
+                                              int32_t logits_dtype, const rlhf_reward_shaping *shaping,
+                                              void *stream)
+{
+    if (!shaping)
+        return rlhf::fail(RLHF_ERR_INVALID, "NULL shaping");
+    if (shaping->penalty != RLHF_PENALTY_FULL_KL && shaping->penalty != RLHF_PENALTY_SAMPLED)
+        return rlhf::fail(RLHF_ERR_INVALID, "penalty %d", shaping->penalty);
+    const rlhf::Shaping sh = {shaping->ref_logp_out, shaping->reward_out, shaping->terminal_scores,
+                              shaping->kl_coef, shaping->penalty == RLHF_PENALTY_SAMPLED};
+    return logprobs_kl_impl(actor_logits, ref_logits, tokens, logp_out, kl_out, n_positions, vocab,
+                            row_stride_elems, logits_dtype, sh, stream);
 }

@@ -25,7 +25,7 @@ def _declared_functions():
 
 def test_library_exports_every_declared_function():
     names = _declared_functions()
-    assert len(names) >= 15
+    assert len(names) >= 16
     L = ctypes.CDLL(rb.LIB_PATH)
     for n in names:
         assert hasattr(L, n), n
@@ -38,6 +38,7 @@ def test_struct_sizes_match_the_header():
     assert ctypes.sizeof(rb.ArenaDesc) == 8 * 4 + 8 + 8 + 8
     assert ctypes.sizeof(rb.ArenaStats) == 4 * 8 + 4 * 4
     assert ctypes.sizeof(rb.AttnParams) == 10 * 4
+    assert ctypes.sizeof(rb.RewardShaping) == 3 * 8 + 2 * 4
 
 
 def _host_arena(**kw):
@@ -146,6 +147,10 @@ def test_compute_entry_points_validate_before_launching():
     with pytest.raises(rb.RlhfError) as e:
         rb.rlhf_token_logprobs_kl(16, 16, 16, 16, 16, n_positions=4, vocab=10, row_stride_elems=8,
                                   logits_dtype=rb.RLHF_F32)
+    assert e.value.status == rb.RLHF_ERR_INVALID
+    with pytest.raises(rb.RlhfError) as e:                       # unknown penalty kind
+        rb.rlhf_token_logprobs_kl_rewards(16, 16, 16, 16, 16, 0.1, penalty=7, n_positions=4, vocab=10,
+                                          logits_dtype=rb.RLHF_F32)
     assert e.value.status == rb.RLHF_ERR_INVALID
 
 

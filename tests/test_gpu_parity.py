@@ -330,3 +330,39 @@ def test_logprobs_full_size_sampled_rows(gu, oracle, cfg_index):
          f"kl {np.abs(kl[rows] - ek).max():.3e}")
     assert np.abs(logp[rows] - el).max() <= LOGP_TOL
     assert np.abs(kl[rows] - ek).max() <= LOGP_TOL
+
+
+@pytest.mark.parametrize("cfg_index,n", [(1, 64), (3, 48), (5, 16)])
+@pytest.mark.parametrize("penalty", [rb.RLHF_PENALTY_FULL_KL, rb.RLHF_PENALTY_SAMPLED])
+def test_reward_shaping_matches_oracle(gu, oracle, cfg_index, n, penalty):
+    """Reference log-prob and KL-penalised per-token reward from the same single
+    pass; padded positions and terminal scores included."""
+    cfg = wl.config(cfg_index)
+    actor, ref = wl.logits(cfg, n_positions=n, device=gu.DEV)
+    tok = wl.tokens(cfg, n_positions=n)
+    tok[5] = -1
+    rng = np.random.default_rng(cfg.seed)
+    term = np.zeros(n, dtype=np.float32)
+    term[[5, n // 2, n - 1]] = rng.standard_normal(3).astype(np.float32)
+    d = lambda a: torch.from_numpy(a).to(gu.DEV)
+    outs = [torch.full((n,), float("nan"), dtype=torch.float32, device=gu.DEV) for _ in range(4)]
+    logp, kl, ref_logp, reward = outs
+    rb.rlhf_token_logprobs_kl_rewards(actor, ref, d(tok), logp, kl, 0.15, penalty=penalty, ref_logp_out=ref_logp,
+                                      reward_out=reward, terminal_scores=d(term))
+    torch.cuda.synchronize()
+    code = wl.DTYPE_CODE[cfg.logits_dtype]
+    el, ek = oracle.token_logprobs_kl(wl.to_storage(actor), wl.to_storage(ref), tok, code)
+    erl, erw = oracle.token_rewards(wl.to_storage(actor), wl.to_storage(ref), tok, code, 0.15,
+                                    penalty == rb.RLHF_PENALTY_SAMPLED, terminal=term.astype(np.float64))
+    got = [t.cpu().numpy().astype(np.float64) for t in outs]
+    for name, g, e in zip(("logp", "kl", "ref_logp", "reward"), got, (el, ek, erl, erw)):
+        err = np.abs(g - e).max()
+        _say(f"  {name}: max-abs err {err:.3e}")
+        assert err <= LOGP_TOL, name
+    assert got[2][5] == 0 and got[3][5] == 0          # padded position: zeros, terminal score ignored
+    # outputs that were not asked for are simply skipped
+    logp2 = torch.empty_like(logp)
+    kl2 = torch.empty_like(kl)
+    rb.rlhf_token_logprobs_kl_rewards(actor, ref, d(tok), logp2, kl2, 0.15, penalty=penalty)
+    torch.cuda.synchronize()
+    assert torch.equal(logp2, logp) and torch.equal(kl2, kl)

@@ -199,3 +199,86 @@ def test_bad_arguments_are_rejected(oracle):
         oracle.token_logprobs_kl(a.astype(np.float64), a, np.zeros(2, dtype=np.int32), F32)
     with pytest.raises(ValueError):
         oracle.token_logprobs_kl(a, a, np.zeros(2, dtype=np.int32), F32, vocab=5)
+
+
+# ------------------------------------------------------------ reward shaping ----
+def test_reference_logprob_closed_form_and_scipy(oracle):
+    """Logits = ln(integers): log p_ref(tok) = ln(r_tok / sum r)."""
+    for line in open(os.path.join(GOLDEN, "kl_closed_forms.txt")):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        name, a, r, tok, _, _ = [f.strip() for f in line.split("|")]
+        ai = [int(x) for x in a.split()]
+        ri = [int(x) for x in r.split()]
+        al = np.log(np.array(ai, dtype=np.float64)).astype(np.float32)[None]
+        rl = np.log(np.array(ri, dtype=np.float64)).astype(np.float32)[None]
+        ref_logp, _ = oracle.token_rewards(al, rl, np.array([int(tok)], dtype=np.int32), F32, 0.0, False)
+        assert abs(ref_logp[0] - math.log(Fraction(ri[int(tok)], sum(ri)))) < 1e-6, name
+    rng = np.random.default_rng(20)
+    a = (rng.standard_normal((6, 300)) * 3).astype(np.float32)
+    r = (rng.standard_normal((6, 300)) * 3).astype(np.float32)
+    tok = rng.integers(0, 300, 6).astype(np.int32)
+    ref_logp, _ = oracle.token_rewards(a, r, tok, F32, 0.0, False)
+    np.testing.assert_allclose(ref_logp, scipy.special.log_softmax(r.astype(np.float64), axis=1)[np.arange(6), tok],
+                               rtol=1e-12)
+
+
+def test_sampled_penalty_averages_to_the_full_kl(oracle):
+    """E_{tok ~ actor}[log p_a(tok) - log p_r(tok)] is the KL of the row: run every
+    token of a small vocabulary through the sampled-penalty reward and average
+    with the actor's probabilities (from scipy)."""
+    rng = np.random.default_rng(21)
+    V = 13
+    a = (rng.standard_normal((1, V)) * 2).astype(np.float32)
+    r = (rng.standard_normal((1, V)) * 2).astype(np.float32)
+    A, R = np.repeat(a, V, axis=0), np.repeat(r, V, axis=0)
+    toks = np.arange(V, dtype=np.int32)
+    _, reward = oracle.token_rewards(A, R, toks, F32, 1.0, True)        # reward = -penalty
+    p = scipy.special.softmax(a.astype(np.float64)[0])
+    _, kl = oracle.token_logprobs_kl(a, r, np.zeros(1, dtype=np.int32), F32)
+    assert abs(-(p * reward).sum() - kl[0]) < 1e-13
+    # and each sampled penalty is the difference of the two log-probabilities
+    logp, _ = oracle.token_logprobs_kl(A, R, toks, F32)
+    ref_logp, _ = oracle.token_rewards(A, R, toks, F32, 0.0, False)
+    np.testing.assert_allclose(-reward, logp - ref_logp, rtol=0, atol=1e-14)
+
+
+def test_reward_is_affine_in_coefficient_and_terminal_score(oracle):
+    rng = np.random.default_rng(22)
+    N, V = 9, 50
+    a = (rng.standard_normal((N, V)) * 2).astype(np.float32)
+    r = (rng.standard_normal((N, V)) * 2).astype(np.float32)
+    tok = rng.integers(0, V, N).astype(np.int32)
+    term = np.zeros(N)
+    term[[2, 8]] = [1.75, -0.5]
+    _, kl = oracle.token_logprobs_kl(a, r, tok, F32)
+    for sampled in (False, True):
+        _, r0 = oracle.token_rewards(a, r, tok, F32, 0.0, sampled, terminal=term)
+        assert np.array_equal(r0, term)                                   # no penalty: the terminal score alone
+        _, r1 = oracle.token_rewards(a, r, tok, F32, 0.1, sampled, terminal=term)
+        _, r2 = oracle.token_rewards(a, r, tok, F32, 0.3, sampled, terminal=term)
+        _, r1n = oracle.token_rewards(a, r, tok, F32, 0.1, sampled)
+        np.testing.assert_allclose(r1 - r1n, term, atol=1e-15)
+        np.testing.assert_allclose((r1 - r2) / 0.2, (r0 - r1) / 0.1, rtol=1e-9, atol=1e-12)
+        if not sampled:
+            np.testing.assert_allclose(r1, term - 0.1 * kl, rtol=1e-13, atol=1e-15)
+            assert (r1n <= 0).all()                                       # full KL is non-negative
+
+
+def test_reward_padding_and_strides(oracle):
+    rng = np.random.default_rng(23)
+    N, V, stride = 4, 20, 24
+    at = torch.from_numpy(rng.standard_normal((N, stride)).astype(np.float32) * 3).to(torch.bfloat16)
+    rt = torch.from_numpy(rng.standard_normal((N, stride)).astype(np.float32) * 3).to(torch.bfloat16)
+    tok = np.array([3, -1, 19, V], dtype=np.int32)
+    term = np.array([0.0, 5.0, 2.0, 5.0])
+    ref_logp, reward = oracle.token_rewards(wl.to_storage(at), wl.to_storage(rt), tok, BF16, 0.2, True,
+                                            terminal=term, vocab=V)
+    assert ref_logp[1] == 0 and reward[1] == 0 and ref_logp[3] == 0 and reward[3] == 0
+    a64, r64 = at.double().numpy()[:, :V], rt.double().numpy()[:, :V]
+    la = scipy.special.log_softmax(a64, axis=1)
+    lr = scipy.special.log_softmax(r64, axis=1)
+    for i in (0, 2):
+        assert abs(ref_logp[i] - lr[i, tok[i]]) < 1e-12
+        assert abs(reward[i] - (term[i] - 0.2 * (la[i, tok[i]] - lr[i, tok[i]]))) < 1e-12

@@ -58,10 +58,24 @@ MUTANTS = [
      "const double lr = load_elem(ref, base + v, dtype) - lse_a;", "logprob"),
     ("kl: weights from the reference", "const double p = exp(la);", "const double p = exp(lr);", "logprob"),
     ("kl: term dropped", "acc += p * (la - lr);", "acc += p * la;", "logprob"),
-    ("logp: gathered at the wrong token", "logp[i] = load_elem(actor, base + (size_t)tok, dtype) - lse_a;",
-     "logp[i] = load_elem(actor, base + (size_t)(tok > 0 ? tok - 1 : 0), dtype) - lse_a;", "logprob"),
-    ("logp: sign", "logp[i] = load_elem(actor, base + (size_t)tok, dtype) - lse_a;",
-     "logp[i] = lse_a - load_elem(actor, base + (size_t)tok, dtype);", "logprob"),
+    ("logp: gathered at the wrong token", "*logp_actor = load_elem(actor, base + (size_t)tok, dtype) - lse_a;",
+     "*logp_actor = load_elem(actor, base + (size_t)(tok > 0 ? tok - 1 : 0), dtype) - lse_a;", "logprob"),
+    ("logp: sign", "*logp_actor = load_elem(actor, base + (size_t)tok, dtype) - lse_a;",
+     "*logp_actor = lse_a - load_elem(actor, base + (size_t)tok, dtype);", "logprob"),
+    ("ref logp: normalised with the actor's lse", "*logp_ref = load_elem(ref, base + (size_t)tok, dtype) - lse_r;",
+     "*logp_ref = load_elem(ref, base + (size_t)tok, dtype) - lse_a;", "logprob"),
+    ("ref logp: gathered from the actor row", "*logp_ref = load_elem(ref, base + (size_t)tok, dtype) - lse_r;",
+     "*logp_ref = load_elem(actor, base + (size_t)tok, dtype) - lse_r;", "logprob"),
+    ("reward: penalty sign", "reward[i] = -kl_coef * penalty + (terminal ? terminal[i] : 0.0);",
+     "reward[i] = kl_coef * penalty + (terminal ? terminal[i] : 0.0);", "logprob"),
+    ("reward: terminal score dropped", "reward[i] = -kl_coef * penalty + (terminal ? terminal[i] : 0.0);",
+     "reward[i] = -kl_coef * penalty;", "logprob"),
+    ("reward: sampled penalty swapped", "const double penalty = sampled_penalty ? lpa - lpr : kl;",
+     "const double penalty = sampled_penalty ? lpr - lpa : kl;", "logprob"),
+    ("reward: penalty modes exchanged", "const double penalty = sampled_penalty ? lpa - lpr : kl;",
+     "const double penalty = sampled_penalty ? kl : lpa - lpr;", "logprob"),
+    ("reward: stride ignored", "score_row(actor, ref, (size_t)i * (size_t)stride, V, dtype, tok, &lpa, &lpr, &kl);",
+     "score_row(actor, ref, (size_t)i * (size_t)V, V, dtype, tok, &lpa, &lpr, &kl);", "logprob"),
     ("logp: base-2 logarithm", "const double lse_a = ma + log(sa);", "const double lse_a = ma + log2(sa);",
      "logprob"),
     ("logp: maximum not added back", "const double lse_a = ma + log(sa);", "const double lse_a = log(sa);",
