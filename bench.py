@@ -77,6 +77,131 @@ def append_bytes(cfg, eb=2):
     return 2 * 2 * cfg.batch * cfg.n_kv_heads * cfg.head_dim * eb   # rows read + written, K and V
 
 
+class Workload:
+    """Inputs of one configuration, resident in HBM, in `n_sets` independent copies
+    (own arena, own logits) that the steps rotate through, so that a small working
+    set is not simply served from the 256 MB last-level cache."""
+
+    def __init__(self, cfg, steps_total, n_sets, dev):
+        import torch
+        from paper_2410_15651_amd import binding as rb
+        from paper_2410_15651_amd import workloads as wl
+        self.cfg, self.rb, self.torch = cfg, rb, torch
+        P = wl.PAGE_TOKENS
+        self.lens = wl.seq_lengths(cfg)
+        self.q, self.ks, self.vs = wl.qkv(cfg, self.lens, device=dev)
+        extra = steps_total + 1
+        self.mpps = cfg.max_pages_per_seq(extra)
+        n_pages = int(((self.lens.astype(np.int64) + extra + P - 1) // P).sum()) + 8
+        order = wl.free_order(cfg, n_pages)
+        kw = dict(max_seqs=cfg.batch, n_kv_heads=cfg.n_kv_heads, head_dim=cfg.head_dim, n_pages=n_pages,
+                  max_pages_per_seq=self.mpps, kv_dtype=wl.DTYPE_CODE[cfg.kv_dtype], initial_free_order=order)
+        self.arena_bytes = rb.rlhf_kv_arena_bytes_required(**kw)
+        self.sets = []
+        for i in range(n_sets):
+            buf = torch.empty(self.arena_bytes, dtype=torch.uint8, device=dev)
+            arena = rb.rlhf_kv_arena_create(device_buffer=buf, device_buffer_bytes=self.arena_bytes, **kw)
+            done = np.zeros(cfg.batch, dtype=np.int64)
+            for ids, n_new in wl.fill_schedule(cfg, self.lens, hold_back=0):
+                k_new = torch.cat([self.ks[b][done[b]:done[b] + n] for b, n in zip(ids, n_new)]).contiguous()
+                v_new = torch.cat([self.vs[b][done[b]:done[b] + n] for b, n in zip(ids, n_new)]).contiguous()
+                rb.rlhf_kv_arena_append(arena, ids, n_new, k_new, v_new)
+                done[ids] += n_new
+            if i == 0:
+                actor, ref = wl.logits(cfg, device=dev)
+            else:                      # same values, different memory
+                actor, ref = self.sets[0]["actor"].clone(), self.sets[0]["ref"].clone()
+            self.sets.append(dict(buf=buf, arena=arena, views=rb.rlhf_kv_arena_views(arena), actor=actor,
+                                  ref=ref, appended=0))
+        g = torch.Generator(device=dev)
+        g.manual_seed(cfg.seed)
+        self.step_k = (torch.randn(cfg.batch, cfg.n_kv_heads, cfg.head_dim, generator=g, device=dev)
+                       * cfg.qkv_std).to(self.q.dtype)
+        self.step_v = (torch.randn(cfg.batch, cfg.n_kv_heads, cfg.head_dim, generator=g, device=dev)
+                       * cfg.qkv_std).to(self.q.dtype)
+        self.tok_np = wl.tokens(cfg)
+        self.tok = torch.from_numpy(self.tok_np).to(dev)
+        n = cfg.n_positions
+        self.logp = torch.empty(n, dtype=torch.float32, device=dev)
+        self.kl = torch.empty(n, dtype=torch.float32, device=dev)
+        self.params = rb.attn_params(cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, self.mpps,
+                                     wl.DTYPE_CODE[cfg.kv_dtype], max_seq_len=cfg.len_hi + extra)
+        self.ws = torch.empty(rb.rlhf_decode_attention_workspace_bytes(self.params), dtype=torch.uint8, device=dev)
+        self.out = torch.empty(cfg.batch, cfg.n_q_heads, cfg.head_dim, dtype=self.q.dtype, device=dev)
+        self.seq_ids = np.arange(cfg.batch, dtype=np.int32)
+        self.ones = np.ones(cfg.batch, dtype=np.int32)
+        torch.cuda.synchronize()
+
+    def step(self, i, marks=None):
+        rb, torch = self.rb, self.torch
+        s = self.sets[i % len(self.sets)]
+        k_arena, v_arena, d_table, d_lens = s["views"]
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(4)] if marks is not None else None
+        if e:
+            e[0].record()
+        rb.rlhf_kv_arena_append(s["arena"], self.seq_ids, self.ones, self.step_k, self.step_v)
+        s["appended"] += 1
+        if e:
+            e[1].record()
+        rb.rlhf_decode_attention(self.params, self.q, k_arena, v_arena, d_table, d_lens, self.out, self.ws)
+        if e:
+            e[2].record()
+        rb.rlhf_token_logprobs_kl(s["actor"], s["ref"], self.tok, self.logp, self.kl)
+        if e:
+            e[3].record()
+            marks.append((e, attention_bytes(self.lens.astype(np.int64) + s["appended"], self.cfg)))
+
+    def close(self):
+        for s in self.sets:
+            self.rb.rlhf_kv_arena_destroy(s["arena"])
+        self.sets = []
+
+
+def rotation_sets(cfg):
+    """Copies needed so that the rotated K/V and the rotated logits each exceed
+    512 MB (more than the last-level cache holds), capped at 12."""
+    lb = 4 if cfg.logits_dtype == "f32" else 2
+    kv = (cfg.len_lo + cfg.len_hi) / 2 * cfg.batch * cfg.n_kv_heads * cfg.head_dim * 2 * 2
+    lg = 2 * cfg.n_positions * cfg.vocab * lb
+    need = max(512e6 / kv, 512e6 / lg)
+    return int(min(12, max(1, np.ceil(need))))
+
+
+def measure(cfg, K, W, dev):
+    """Times K steps after W warm-up steps; returns the numbers of one configuration."""
+    import torch
+    lb = 4 if cfg.logits_dtype == "f32" else 2
+    n_sets = rotation_sets(cfg)
+    t0 = time.time()
+    wk = Workload(cfg, K + W, n_sets, dev)
+    log(f"setup {time.time() - t0:.1f}s: cfg{cfg.index} {cfg.name}, {n_sets} rotating input set(s), K/V "
+        f"{2 * wk.lens.sum() * cfg.n_kv_heads * cfg.head_dim * 2 / 1e9:.3f} GB, logits "
+        f"{2 * cfg.n_positions * cfg.vocab * lb / 1e9:.2f} GB, arena reserved {wk.arena_bytes / 1e9:.3f} GB each")
+    for i in range(W):
+        wk.step(i)
+    torch.cuda.synchronize()
+    marks = []
+    t_start = time.perf_counter()
+    for i in range(K):
+        wk.step(W + i, marks)
+    torch.cuda.synchronize()
+    t_total = time.perf_counter() - t_start
+    t_append = np.array([m[0][0].elapsed_time(m[0][1]) for m in marks]) * 1e-3
+    t_attn = np.array([m[0][1].elapsed_time(m[0][2]) for m in marks]) * 1e-3
+    t_logp = np.array([m[0][2].elapsed_time(m[0][3]) for m in marks]) * 1e-3
+    b_attn = float(np.mean([m[1] for m in marks]))
+    b_logp = logprob_bytes(cfg.n_positions, cfg.vocab, lb)
+    b_step = b_attn + b_logp + append_bytes(cfg)
+    kv_rotated = n_sets * 2 * wk.lens.sum() * cfg.n_kv_heads * cfg.head_dim * 2
+    res = dict(
+        wk=wk, n_sets=n_sets, t_total=t_total, b_step=b_step, b_attn=b_attn, b_logp=b_logp, lb=lb,
+        ms_per_step=t_total / K * 1e3, value=b_step / (t_total / K) / 1e9,
+        attn_gbps=b_attn / t_attn.mean() / 1e9, logp_gbps=b_logp / t_logp.mean() / 1e9,
+        attn_us=t_attn.mean() * 1e6, logp_us=t_logp.mean() * 1e6, append_us=t_append.mean() * 1e6,
+        attn_cold=bool(kv_rotated > 512e6), stats=wk.rb.rlhf_kv_arena_stats(wk.sets[0]["arena"]))
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -84,6 +209,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=5, help="workload index 1..5 (default: the largest)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="skip the short per-kernel summary of the other four configurations")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain 1 GiB device-to-device copies first (a kernel of known "
                          "traffic, to scale hardware byte counters in a rocprofv3 --pmc run)")
@@ -112,98 +239,14 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    P = wl.PAGE_TOKENS
-    eb = 2
-    lb = 4 if cfg.logits_dtype == "f32" else 2
 
-    # ---------------- inputs, resident in HBM ----------------
-    t0 = time.time()
-    lens = wl.seq_lengths(cfg)
-    q, ks, vs = wl.qkv(cfg, lens, device=dev)
-    extra = K + W + 1
-    mpps = cfg.max_pages_per_seq(extra)
-    n_pages = int(((lens.astype(np.int64) + extra + P - 1) // P).sum()) + 8
-    order = wl.free_order(cfg, n_pages)
-    kw = dict(max_seqs=cfg.batch, n_kv_heads=cfg.n_kv_heads, head_dim=cfg.head_dim, n_pages=n_pages,
-              max_pages_per_seq=mpps, kv_dtype=wl.DTYPE_CODE[cfg.kv_dtype], initial_free_order=order)
-    arena_bytes = rb.rlhf_kv_arena_bytes_required(**kw)
-    arena_buf = torch.empty(arena_bytes, dtype=torch.uint8, device=dev)
-    arena = rb.rlhf_kv_arena_create(device_buffer=arena_buf, device_buffer_bytes=arena_bytes, **kw)
-    done = np.zeros(cfg.batch, dtype=np.int64)
-    for ids, n_new in wl.fill_schedule(cfg, lens, hold_back=0):
-        k_new = torch.cat([ks[b][done[b]:done[b] + n] for b, n in zip(ids, n_new)]).contiguous()
-        v_new = torch.cat([vs[b][done[b]:done[b] + n] for b, n in zip(ids, n_new)]).contiguous()
-        rb.rlhf_kv_arena_append(arena, ids, n_new, k_new, v_new)
-        done[ids] += n_new
-    torch.cuda.synchronize()
-    g = torch.Generator(device=dev)
-    g.manual_seed(cfg.seed)
-    step_k = (torch.randn(cfg.batch, cfg.n_kv_heads, cfg.head_dim, generator=g, device=dev) * cfg.qkv_std
-              ).to(q.dtype)
-    step_v = (torch.randn(cfg.batch, cfg.n_kv_heads, cfg.head_dim, generator=g, device=dev) * cfg.qkv_std
-              ).to(q.dtype)
-    actor, ref = wl.logits(cfg, device=dev)
-    tok_np = wl.tokens(cfg)
-    tok = torch.from_numpy(tok_np).to(dev)
+    m = measure(cfg, K, W, dev)
+    wk, stats = m["wk"], m["stats"]
     n_pos = cfg.n_positions
-    logp = torch.empty(n_pos, dtype=torch.float32, device=dev)
-    kl = torch.empty(n_pos, dtype=torch.float32, device=dev)
-    k_arena, v_arena, d_table, d_lens = rb.rlhf_kv_arena_views(arena)
-    params = rb.attn_params(cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, mpps,
-                            wl.DTYPE_CODE[cfg.kv_dtype], max_seq_len=cfg.len_hi + extra)
-    ws = torch.empty(rb.rlhf_decode_attention_workspace_bytes(params), dtype=torch.uint8, device=dev)
-    out = torch.empty(cfg.batch, cfg.n_q_heads, cfg.head_dim, dtype=q.dtype, device=dev)
-    seq_ids = np.arange(cfg.batch, dtype=np.int32)
-    ones = np.ones(cfg.batch, dtype=np.int32)
-    torch.cuda.synchronize()
-    log(f"setup {time.time() - t0:.1f}s: cfg{cfg.index} {cfg.name} K/V {2 * lens.sum() * cfg.n_kv_heads * cfg.head_dim * eb / 1e9:.3f} GB, "
-        f"logits {2 * n_pos * cfg.vocab * lb / 1e9:.2f} GB, arena reserved {arena_bytes / 1e9:.3f} GB")
-
-    ev = lambda: torch.cuda.Event(enable_timing=True)
-    marks = []
-
-    def step(record):
-        if record:
-            e = [ev() for _ in range(4)]
-            e[0].record()
-        rb.rlhf_kv_arena_append(arena, seq_ids, ones, step_k, step_v)
-        if record:
-            e[1].record()
-        rb.rlhf_decode_attention(params, q, k_arena, v_arena, d_table, d_lens, out, ws)
-        if record:
-            e[2].record()
-        rb.rlhf_token_logprobs_kl(actor, ref, tok, logp, kl)
-        if record:
-            e[3].record()
-            marks.append(e)
-
-    for _ in range(W):
-        step(False)
-    torch.cuda.synchronize()
-    cur_lens = lens.astype(np.int64) + W
-    step_attn_bytes = []
-    t_start = time.perf_counter()
-    for i in range(K):
-        step(True)
-        step_attn_bytes.append(attention_bytes(cur_lens + i + 1, cfg, eb))
-    torch.cuda.synchronize()
-    t_total = time.perf_counter() - t_start
-
-    t_append = np.array([m[0].elapsed_time(m[1]) for m in marks]) * 1e-3
-    t_attn = np.array([m[1].elapsed_time(m[2]) for m in marks]) * 1e-3
-    t_logp = np.array([m[2].elapsed_time(m[3]) for m in marks]) * 1e-3
-    b_attn = float(np.mean(step_attn_bytes))
-    b_logp = logprob_bytes(n_pos, cfg.vocab, lb)
-    b_step = b_attn + b_logp + append_bytes(cfg, eb)
-    ms_per_step = t_total / K * 1e3
-    value = b_step / (t_total / K) / 1e9
-    attn_gbps = b_attn / t_attn.mean() / 1e9
-    logp_gbps = b_logp / t_logp.mean() / 1e9
-    stats = rb.rlhf_kv_arena_stats(arena)
-
+    attn_kernel = ("attn_stream_kernel" if cfg.n_q_heads == cfg.n_kv_heads else "attn_stream_gqa_kernel")
     result = {
-        "metric": METRIC, "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": K, "warmup": W,
-        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "metric": METRIC, "value": round(m["value"], 1), "unit": "GB/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": round(m["ms_per_step"], 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32 accumulate (bf16/f16 storage)", "data": "synthetic",
         "config": {"workload": f"configs[{cfg.index - 1}] {cfg.name}: batch {cfg.batch}, {cfg.n_q_heads}q/"
                                f"{cfg.n_kv_heads}kv heads, head_dim {cfg.head_dim}, {cfg.kv_dtype} KV, cache "
@@ -211,30 +254,54 @@ def main():
                                f"{'shuffled' if cfg.shuffled_pages else 'in order'}; logprob/KL {n_pos} positions x "
                                f"vocab {cfg.vocab}, {cfg.logits_dtype} logits",
                    "step": "append 1 token/seq + decode attention + token logprob/KL",
-                   "accumulate": "fp32", "hbm_peak_GBps": HBM_PEAK_GBPS},
+                   "accumulate": "fp32", "hbm_peak_GBps": HBM_PEAK_GBPS, "rotating_input_sets": m["n_sets"]},
         "components": {
-            "decode_attn_GBps": round(attn_gbps, 1), "decode_attn_frac_of_peak": round(attn_gbps / HBM_PEAK_GBPS, 4),
-            "decode_attn_us": round(t_attn.mean() * 1e6, 2), "decode_attn_bytes": int(b_attn),
-            "logprob_kl_tokens_per_s": round(n_pos / t_logp.mean(), 1), "logprob_kl_GBps": round(logp_gbps, 1),
-            "logprob_kl_frac_of_peak": round(logp_gbps / HBM_PEAK_GBPS, 4),
-            "logprob_kl_us": round(t_logp.mean() * 1e6, 2), "append_us": round(t_append.mean() * 1e6, 2),
+            "decode_attn_GBps": round(m["attn_gbps"], 1),
+            "decode_attn_frac_of_peak": round(m["attn_gbps"] / HBM_PEAK_GBPS, 4),
+            "decode_attn_us": round(m["attn_us"], 2), "decode_attn_bytes": int(m["b_attn"]),
+            "logprob_kl_tokens_per_s": round(n_pos / (m["logp_us"] * 1e-6), 1),
+            "logprob_kl_GBps": round(m["logp_gbps"], 1),
+            "logprob_kl_frac_of_peak": round(m["logp_gbps"] / HBM_PEAK_GBPS, 4),
+            "logprob_kl_us": round(m["logp_us"], 2), "append_us": round(m["append_us"], 2),
             "arena_reserved_bytes": stats["reserved_bytes"], "arena_allocated_bytes": stats["allocated_bytes"],
             "arena_driver_allocations_after_create": 0,
         },
-        "roofline": {"kernel": "logprob_kl_kernel", "bound": "hbm", "achieved": round(logp_gbps, 1),
-                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(logp_gbps / HBM_PEAK_GBPS, 4),
+        "roofline": {"kernel": "logprob_kl_kernel", "bound": "hbm", "achieved": round(m["logp_gbps"], 1),
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(m["logp_gbps"] / HBM_PEAK_GBPS, 4),
                      "traffic": measured_traffic("logprob_kl", cfg.index)},
-        "roofline_decode_attn": {"kernel": ("attn_stream_kernel" if cfg.n_q_heads == cfg.n_kv_heads
-                                            else "attn_stream_gqa_kernel") + "+attn_merge_kernel",
-                                 "bound": "hbm",
-                                 "achieved": round(attn_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                                 "frac": round(attn_gbps / HBM_PEAK_GBPS, 4),
+        "roofline_decode_attn": {"kernel": attn_kernel + "+attn_merge_kernel", "bound": "hbm",
+                                 "achieved": round(m["attn_gbps"], 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                                 "frac": round(m["attn_gbps"] / HBM_PEAK_GBPS, 4),
                                  "traffic": measured_traffic("decode_attn", cfg.index)},
     }
-
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(cfg, lens, q, ks, vs, actor, ref, tok_np, b_step, lb, eb)
-    rb.rlhf_kv_arena_destroy(arena)
+        result["cpu_baseline"] = cpu_baseline(cfg, wk.lens, wk.q, wk.ks, wk.vs, wk.sets[0]["actor"],
+                                              wk.sets[0]["ref"], wk.tok_np, m["b_step"], m["lb"], 2)
+    wk.close()
+    del wk, m
+    torch.cuda.empty_cache()
+
+    if not args.no_other_configs:
+        others = []
+        for c in wl.CONFIGS:
+            if c.index == cfg.index:
+                continue
+            o = measure(c, 10, 2, dev)
+            others.append({
+                "workload": f"configs[{c.index - 1}] {c.name}", "rotating_input_sets": o["n_sets"],
+                "decode_attn_us": round(o["attn_us"], 2), "decode_attn_GBps": round(o["attn_gbps"], 1),
+                "decode_attn_frac_of_peak": round(o["attn_gbps"] / HBM_PEAK_GBPS, 4),
+                "decode_attn_reads": "cold (rotated past the last-level cache)" if o["attn_cold"]
+                                     else "cache-resident: the call is launch-latency-bound",
+                "logprob_kl_us": round(o["logp_us"], 2),
+                "logprob_kl_tokens_per_s": round(c.n_positions / (o["logp_us"] * 1e-6), 1),
+                "logprob_kl_GBps": round(o["logp_gbps"], 1),
+                "logprob_kl_frac_of_peak": round(o["logp_gbps"] / HBM_PEAK_GBPS, 4),
+                "append_us": round(o["append_us"], 2), "step_GBps": round(o["value"], 1)})
+            o["wk"].close()
+            del o
+            torch.cuda.empty_cache()
+        result["other_configs"] = others
     print(json.dumps(result), flush=True)
 
 

@@ -185,7 +185,8 @@ int rlhf_kv_arena_gather(const rlhf_kv_arena *arena, int32_t seq_id, int32_t sta
  *   out        dev [batch][n_q_heads][head_dim], out_dtype (round to nearest even)
  *   workspace  dev, >= rlhf_decode_attention_workspace_bytes, 16-byte aligned;
  *              scratch for split partials, contents undefined afterwards
- * q, k_arena, v_arena and out must be 16-byte aligned.
+ * q, k_arena, v_arena and out must be 16-byte aligned.  batch may not exceed
+ * 8192 per call (RLHF_ERR_UNSUPPORTED; split larger batches).
  * ------------------------------------------------------------------------ */
 typedef struct {
     int32_t batch;

@@ -43,6 +43,8 @@
 
 #include <algorithm>
 #include <cmath>
+#include <mutex>
+#include <vector>
 
 #include "common.h"
 #include "device_ops.h"
@@ -701,16 +703,40 @@ int check_params(const rlhf_attn_params *p)
     return RLHF_OK;
 }
 
-// Wavefronts the device can hold at once for a kernel, capped by the sizing bound.
+// Wavefronts the device can hold at once for a kernel, capped by the sizing
+// bound.  The occupancy query is remembered per (device, kernel, LDS bytes).
+struct ResidentEntry {
+    int device;
+    const void *kernel;
+    size_t lds;
+    int waves;
+};
+std::mutex g_resident_mutex;
+std::vector<ResidentEntry> g_resident;
+
 template <typename Kernel>
 int resident_waves(Kernel kernel, size_t lds_bytes, int bound, int *out)
 {
-    int dev = 0, cus = 0, blocks = 0;
+    int dev = 0;
     RLHF_HIP_TRY(hipGetDevice(&dev));
+    const void *key = reinterpret_cast<const void *>(kernel);
+    {
+        std::lock_guard<std::mutex> lock(g_resident_mutex);
+        for (const auto &e : g_resident)
+            if (e.device == dev && e.kernel == key && e.lds == lds_bytes) {
+                *out = std::min(e.waves, bound);
+                return RLHF_OK;
+            }
+    }
+    int cus = 0, blocks = 0;
     RLHF_HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
     RLHF_HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, kernel, kThreads, lds_bytes));
-    const int64_t waves = (int64_t)cus * std::max(blocks, 1) * kWgWaves;
-    *out = (int)std::min<int64_t>(waves, bound);
+    const int waves = (int)std::min<int64_t>((int64_t)cus * std::max(blocks, 1) * kWgWaves, 1 << 20);
+    {
+        std::lock_guard<std::mutex> lock(g_resident_mutex);
+        g_resident.push_back({dev, key, lds_bytes, waves});
+    }
+    *out = std::min(waves, bound);
     return RLHF_OK;
 }
 
