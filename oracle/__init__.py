@@ -70,6 +70,13 @@ class OracleLib:
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
             ctypes.c_void_p, ctypes.c_void_p,
             ctypes.c_int64, ctypes.c_int, ctypes.c_int64, ctypes.c_int, ctypes.c_double, ctypes.c_int]
+        lib.oracle_philox4x32_10.restype = None
+        lib.oracle_philox4x32_10.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+        lib.oracle_sample_tokens.restype = ctypes.c_int
+        lib.oracle_sample_tokens.argtypes = [
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_int64, ctypes.c_int, ctypes.c_int64, ctypes.c_int,
+            ctypes.c_double, ctypes.c_uint64, ctypes.c_uint64]
         self._lib = lib
 
     def num_threads(self) -> int:
@@ -149,6 +156,33 @@ class OracleLib:
         return ref_logp, reward
 
 
+    def philox4x32_10(self, ctr, key):
+        c = np.ascontiguousarray(ctr, dtype=np.uint32)
+        k = np.ascontiguousarray(key, dtype=np.uint32)
+        assert c.shape == (4,) and k.shape == (2,)
+        out = np.zeros(4, dtype=np.uint32)
+        self._lib.oracle_philox4x32_10(c.ctypes.data, k.ctypes.data, out.ctypes.data)
+        return out
+
+    def sample_tokens(self, logits, dtype, temperature, seed, offset=0, vocab=None,
+                      return_perturbed=False):
+        """logits [N,stride] -> (tokens [N] int32, logp [N] float64[, perturbed [N,V]])."""
+        logits = _storage(logits, dtype)
+        assert logits.ndim == 2
+        N, stride = logits.shape
+        V = stride if vocab is None else int(vocab)
+        tokens = np.zeros(N, dtype=np.int32)
+        logp = np.zeros(N, dtype=np.float64)
+        pert = np.zeros((N, V), dtype=np.float64) if return_perturbed else None
+        rc = self._lib.oracle_sample_tokens(
+            logits.ctypes.data, tokens.ctypes.data, logp.ctypes.data,
+            pert.ctypes.data if return_perturbed else None, N, V, stride, dtype,
+            float(temperature), int(seed), int(offset))
+        if rc != 0:
+            raise ValueError("oracle_sample_tokens rejected its arguments")
+        return (tokens, logp, pert) if return_perturbed else (tokens, logp)
+
+
 _default = None
 
 
@@ -173,6 +207,14 @@ def token_logprobs_kl(*args, **kw):
 
 def token_rewards(*args, **kw):
     return _load().token_rewards(*args, **kw)
+
+
+def philox4x32_10(*args, **kw):
+    return _load().philox4x32_10(*args, **kw)
+
+
+def sample_tokens(*args, **kw):
+    return _load().sample_tokens(*args, **kw)
 
 
 decode_attention.__doc__ = OracleLib.decode_attention.__doc__

@@ -20,6 +20,8 @@
  *                             the whole vocabulary
  *   oracle_token_rewards      the reference model's log-probability of the
  *                             token and the KL-penalised per-token reward
+ *   oracle_sample_tokens      next-token sampling from softmax(logits / T) by
+ *                             Gumbel-max over counter-based (Philox) uniforms
  *
  * Inputs arrive in their storage precision (IEEE binary16, bfloat16 or
  * binary32) and are widened exactly to double; every sum, exponential and
@@ -291,6 +293,92 @@ int oracle_token_rewards(const void *actor, const void *ref, const int32_t *toke
         const double penalty = sampled_penalty ? lpa - lpr : kl;
         ref_logp[i] = lpr;
         reward[i] = -kl_coef * penalty + (terminal ? terminal[i] : 0.0);
+    }
+    return 0;
+}
+
+/*
+ * Philox4x32-10 (Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as easy
+ * as 1, 2, 3", SC'11), written from the published definition: ten rounds of
+ *   (c0,c1,c2,c3) <- (hi(M1*c2) ^ c1 ^ k0, lo(M1*c2), hi(M0*c0) ^ c3 ^ k1, lo(M0*c0))
+ * with the key advanced by the Weyl constants between rounds.
+ */
+void oracle_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4])
+{
+    const uint64_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u;
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+    uint32_t k0 = key[0], k1 = key[1];
+    for (int round = 0; round < 10; ++round) {
+        const uint64_t p0 = M0 * c0, p1 = M1 * c2;
+        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        const uint32_t n1 = (uint32_t)p1;
+        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        const uint32_t n3 = (uint32_t)p0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* The uniform on (0,1) that vocabulary entry v of row i gets: 24 bits of word
+ * v%4 of Philox(counter = (v/4, i, offset low, offset high), key = seed). */
+static double sampling_uniform(int64_t row, int v, uint64_t seed, uint64_t offset)
+{
+    const uint32_t ctr[4] = {(uint32_t)(v / 4), (uint32_t)row, (uint32_t)offset, (uint32_t)(offset >> 32)};
+    const uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+    uint32_t r[4];
+    oracle_philox4x32_10(ctr, key, r);
+    return ((double)(r[v % 4] >> 8) + 0.5) * (1.0 / 16777216.0);
+}
+
+/*
+ * Sampling the next token from the actor's logits (Section 2.1: "the actor
+ * generates responses").  With temperature T > 0 the token is drawn from
+ * softmax(logits / T) by the Gumbel-max construction:
+ *     token = argmax_v ( logits_v / T + G_v ),   G_v = -ln(-ln u_v)
+ * with u_v the counter-based uniforms above; T == 0 means greedy argmax.  Ties
+ * go to the lowest index.  logp = log softmax(logits / T)[token] (T = 1 for
+ * greedy).  perturbed_out, if not NULL, receives every logits_v / T + G_v
+ * ([N][V]), which lets a test accept any token whose perturbed score is within
+ * rounding of the maximum.
+ */
+int oracle_sample_tokens(const void *logits, int32_t *tokens, double *logp, double *perturbed_out,
+                         int64_t N, int V, int64_t stride, int dtype,
+                         double temperature, uint64_t seed, uint64_t offset)
+{
+    if (!logits || !tokens || !logp || N < 0 || V <= 0 || temperature < 0.0)
+        return -1;
+    if (stride == 0)
+        stride = V;
+    if (stride < V)
+        return -1;
+    const double inv_t = temperature > 0.0 ? 1.0 / temperature : 1.0;
+
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < N; ++i) {
+        const size_t base = (size_t)i * (size_t)stride;
+        int best = 0;
+        double best_z = -INFINITY, m = -INFINITY;
+        for (int v = 0; v < V; ++v) {
+            const double y = load_elem(logits, base + v, dtype) * inv_t;
+            double z = y;
+            if (temperature > 0.0)
+                z += -log(-log(sampling_uniform(i, v, seed, offset)));
+            if (perturbed_out)
+                perturbed_out[(size_t)i * V + v] = z;
+            if (z > best_z) {
+                best_z = z;
+                best = v;
+            }
+            if (y > m)
+                m = y;
+        }
+        double s = 0.0;
+        for (int v = 0; v < V; ++v)
+            s += exp(load_elem(logits, base + v, dtype) * inv_t - m);
+        tokens[i] = best;
+        logp[i] = load_elem(logits, base + (size_t)best, dtype) * inv_t - (m + log(s));
     }
     return 0;
 }

@@ -1,7 +1,7 @@
 """Are the oracle's pins strong enough?  Each case plants one plausible mistake
 in a copy of the oracle's C source (on the CPU, in a temporary directory),
-builds it, and runs the pin tests of test_oracle_attention.py and
-test_oracle_logprob_kl.py against the copy.  Every planted mistake must make at
+builds it, and runs the pin tests of test_oracle_attention.py,
+test_oracle_logprob_kl.py and test_oracle_sampling.py against the copy.  Every planted mistake must make at
 least one pin fail; the unmodified source must pass them all."""
 import inspect
 import os
@@ -11,6 +11,7 @@ import pytest
 import oracle as oracle_pkg
 import test_oracle_attention as pins_attention
 import test_oracle_logprob_kl as pins_logprob
+import test_oracle_sampling as pins_sampling
 
 SRC = os.path.join(os.path.dirname(oracle_pkg.__file__), "rollout_oracle.c")
 
@@ -82,14 +83,31 @@ MUTANTS = [
      "logprob"),
     ("rows: stride ignored", "const size_t base = (size_t)i * (size_t)stride;",
      "const size_t base = (size_t)i * (size_t)V;", "logprob"),
+    ("philox: nine rounds", "for (int round = 0; round < 10; ++round) {", "for (int round = 0; round < 9; ++round) {",
+     "sampling"),
+    ("philox: multipliers exchanged", "const uint64_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u;",
+     "const uint64_t M0 = 0xCD9E8D57u, M1 = 0xD2511F53u;", "sampling"),
+    ("philox: key not advanced", "        k1 += 0xBB67AE85u;\n", "", "sampling"),
+    ("sampling: wrong word of the block", "return ((double)(r[v % 4] >> 8) + 0.5)",
+     "return ((double)(r[(v + 1) % 4] >> 8) + 0.5)", "sampling"),
+    ("sampling: row not in the counter", "(uint32_t)(v / 4), (uint32_t)row, (uint32_t)offset",
+     "(uint32_t)(v / 4), 0u, (uint32_t)offset", "sampling"),
+    ("sampling: noise sign", "z += -log(-log(sampling_uniform(i, v, seed, offset)));",
+     "z += log(-log(sampling_uniform(i, v, seed, offset)));", "sampling"),
+    ("sampling: temperature ignored", "const double inv_t = temperature > 0.0 ? 1.0 / temperature : 1.0;",
+     "const double inv_t = 1.0 + 0.0 * temperature;", "sampling"),
+    ("sampling: ties to the last index", "            if (z > best_z) {", "            if (z >= best_z) {",
+     "sampling"),
+    ("sampling: logp without the temperature", "s += exp(load_elem(logits, base + v, dtype) * inv_t - m);",
+     "s += exp(load_elem(logits, base + v, dtype) - m);", "sampling"),
     ("padding: not zeroed", "            logp[i] = 0.0;\n            kl[i] = 0.0;\n            continue;",
      "            logp[i] = -1.0;\n            kl[i] = 0.0;\n            continue;", "logprob"),
 ]
 
 
 def _pins(which):
-    mods = {"attention": [pins_attention], "logprob": [pins_logprob],
-            "both": [pins_attention, pins_logprob]}[which]
+    mods = {"attention": [pins_attention], "logprob": [pins_logprob], "sampling": [pins_sampling],
+            "both": [pins_attention, pins_logprob], "all": [pins_attention, pins_logprob, pins_sampling]}[which]
     out = []
     for mod in mods:
         for name, fn in sorted(vars(mod).items()):
@@ -117,8 +135,8 @@ def _first_failure(lib, pins):
 
 def test_unmodified_copy_passes_every_pin(tmp_path):
     lib = _build_variant(tmp_path, open(SRC).read(), "clean")
-    assert len(_pins("both")) >= 30
-    assert _first_failure(lib, _pins("both")) is None
+    assert len(_pins("all")) >= 40
+    assert _first_failure(lib, _pins("all")) is None
 
 
 @pytest.mark.parametrize("name,find,replace,which", MUTANTS, ids=[m[0] for m in MUTANTS])

@@ -1,0 +1,100 @@
+"""Pins for the sampling oracle: Philox known-answer vectors, the counter
+convention, greedy = argmax, Gumbel-max frequencies against softmax, noise
+moments, log-prob via scipy, determinism."""
+import math
+import os
+
+import numpy as np
+import scipy.special
+import scipy.stats
+
+F32 = 2
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def test_philox_known_answers(oracle):
+    n = 0
+    for line in open(os.path.join(GOLDEN, "philox4x32_10_kat.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        ctr, key, out = [[int(w, 16) for w in part.split()] for part in line.split("|")]
+        assert oracle.philox4x32_10(ctr, key).tolist() == out
+        n += 1
+    assert n == 3
+
+
+def test_counter_convention_and_gumbel_transform(oracle):
+    """Zero logits, T = 1: the perturbed score is the noise itself, and entry v
+    of row i uses word v%4 of Philox(counter (v/4, i, offset lo, offset hi), key = seed)."""
+    V, N = 11, 3
+    seed, offset = 0x1234567890ABCDEF, (7 << 32) | 5
+    _, _, pert = oracle.sample_tokens(np.zeros((N, V), dtype=np.float32), F32, 1.0, seed, offset,
+                                      return_perturbed=True)
+    for i in range(N):
+        for v in range(V):
+            r = oracle.philox4x32_10([v // 4, i, offset & 0xffffffff, offset >> 32],
+                                     [seed & 0xffffffff, seed >> 32])
+            u = ((int(r[v % 4]) >> 8) + 0.5) / 2 ** 24
+            assert abs(pert[i, v] - (-math.log(-math.log(u)))) < 1e-12
+
+
+def test_greedy_is_argmax_with_lowest_index_ties(oracle):
+    rng = np.random.default_rng(0)
+    a = (rng.standard_normal((20, 300)) * 3).astype(np.float32)
+    a[3, 17] = a[3, 200] = 50.0
+    tok, logp = oracle.sample_tokens(a, F32, 0.0, 1)
+    assert tok.tolist() == a.argmax(axis=1).tolist() and tok[3] == 17
+    np.testing.assert_allclose(logp, scipy.special.log_softmax(a.astype(np.float64), axis=1)[np.arange(20), tok],
+                               rtol=1e-12)
+
+
+def test_gumbel_max_frequencies_follow_softmax(oracle):
+    logits = np.array([0.0, 1.0, -1.0, 2.5, 0.3, -3.0], dtype=np.float32)
+    N = 60000
+    for T in (1.0, 0.7, 2.0):
+        tok, logp = oracle.sample_tokens(np.tile(logits, (N, 1)), F32, T, 99, 3)
+        p = scipy.special.softmax(logits.astype(np.float64) / T)
+        counts = np.bincount(tok, minlength=6)
+        chi2 = ((counts - N * p) ** 2 / (N * p)).sum()
+        assert chi2 < scipy.stats.chi2.ppf(1 - 1e-6, 5), (T, chi2)
+        np.testing.assert_allclose(logp, np.log(p)[tok], rtol=1e-12)
+
+
+def test_noise_is_independent_of_the_logits_and_has_gumbel_moments(oracle):
+    rng = np.random.default_rng(1)
+    a = rng.standard_normal((40, 500)).astype(np.float32)
+    b = rng.standard_normal((40, 500)).astype(np.float32)
+    ta, _, pa = oracle.sample_tokens(a, F32, 0.5, 5, 11, return_perturbed=True)
+    tb, _, pb = oracle.sample_tokens(b, F32, 0.5, 5, 11, return_perturbed=True)
+    noise = pa - a.astype(np.float64) / 0.5
+    np.testing.assert_allclose(noise, pb - b.astype(np.float64) / 0.5, atol=1e-12)
+    assert ta.tolist() == pa.argmax(axis=1).tolist()
+    assert abs(noise.mean() - 0.5772156649) < 0.02 and abs(noise.var() - math.pi ** 2 / 6) < 0.05
+    assert np.isfinite(noise).all()
+
+
+def test_seed_offset_row_and_temperature_matter(oracle):
+    a = np.zeros((64, 1000), dtype=np.float32)
+    t0, _ = oracle.sample_tokens(a, F32, 1.0, 1, 0)
+    t1, _ = oracle.sample_tokens(a, F32, 1.0, 1, 0)
+    assert t0.tolist() == t1.tolist()                       # deterministic
+    assert len(set(t0.tolist())) > 40                       # rows get different noise
+    assert t0.tolist() != oracle.sample_tokens(a, F32, 1.0, 2, 0)[0].tolist()
+    assert t0.tolist() != oracle.sample_tokens(a, F32, 1.0, 1, 1)[0].tolist()
+    rng = np.random.default_rng(2)
+    b = (rng.standard_normal((200, 50)) * 2).astype(np.float32)
+    cold, _ = oracle.sample_tokens(b, F32, 0.01, 3)
+    assert (cold == b.argmax(axis=1)).mean() > 0.97         # T -> 0 approaches greedy
+    hot, _ = oracle.sample_tokens(b, F32, 100.0, 3)
+    assert (hot == b.argmax(axis=1)).mean() < 0.2           # T -> inf approaches uniform
+
+
+def test_strides_and_16bit_inputs(oracle):
+    import torch
+    from paper_2410_15651_amd import workloads as wl
+    rng = np.random.default_rng(3)
+    t = torch.from_numpy(rng.standard_normal((6, 24)).astype(np.float32) * 3).to(torch.bfloat16)
+    tok, logp, pert = oracle.sample_tokens(wl.to_storage(t), 1, 0.8, 4, 0, vocab=20, return_perturbed=True)
+    x = t.double().numpy()[:, :20] / 0.8
+    assert pert.shape == (6, 20) and tok.tolist() == pert.argmax(axis=1).tolist()
+    np.testing.assert_allclose(logp, scipy.special.log_softmax(x, axis=1)[np.arange(6), tok], rtol=1e-12)
