@@ -321,15 +321,17 @@ void oracle_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t
     out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
 }
 
-/* The uniform on (0,1) that vocabulary entry v of row i gets: 24 bits of word
- * v%4 of Philox(counter = (v/4, i, offset low, offset high), key = seed). */
+/* The uniform on (0,1) that vocabulary entry v of row i gets: the top 23 bits of
+ * word v%4 of Philox(counter = (v/4, i, offset low, offset high), key = seed),
+ * centred in their cell.  23 bits because (k + 1/2) / 2^23 is then exact in
+ * binary32, the precision the sampled decision is taken in on the GPU. */
 static double sampling_uniform(int64_t row, int v, uint64_t seed, uint64_t offset)
 {
     const uint32_t ctr[4] = {(uint32_t)(v / 4), (uint32_t)row, (uint32_t)offset, (uint32_t)(offset >> 32)};
     const uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
     uint32_t r[4];
     oracle_philox4x32_10(ctr, key, r);
-    return ((double)(r[v % 4] >> 8) + 0.5) * (1.0 / 16777216.0);
+    return ((double)(r[v % 4] >> 9) + 0.5) * (1.0 / 8388608.0);
 }
 
 /*

@@ -88,8 +88,8 @@ MUTANTS = [
     ("philox: multipliers exchanged", "const uint64_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u;",
      "const uint64_t M0 = 0xCD9E8D57u, M1 = 0xD2511F53u;", "sampling"),
     ("philox: key not advanced", "        k1 += 0xBB67AE85u;\n", "", "sampling"),
-    ("sampling: wrong word of the block", "return ((double)(r[v % 4] >> 8) + 0.5)",
-     "return ((double)(r[(v + 1) % 4] >> 8) + 0.5)", "sampling"),
+    ("sampling: wrong word of the block", "return ((double)(r[v % 4] >> 9) + 0.5)",
+     "return ((double)(r[(v + 1) % 4] >> 9) + 0.5)", "sampling"),
     ("sampling: row not in the counter", "(uint32_t)(v / 4), (uint32_t)row, (uint32_t)offset",
      "(uint32_t)(v / 4), 0u, (uint32_t)offset", "sampling"),
     ("sampling: noise sign", "z += -log(-log(sampling_uniform(i, v, seed, offset)));",

@@ -34,7 +34,7 @@ def test_counter_convention_and_gumbel_transform(oracle):
         for v in range(V):
             r = oracle.philox4x32_10([v // 4, i, offset & 0xffffffff, offset >> 32],
                                      [seed & 0xffffffff, seed >> 32])
-            u = ((int(r[v % 4]) >> 8) + 0.5) / 2 ** 24
+            u = ((int(r[v % 4]) >> 9) + 0.5) / 2 ** 23
             assert abs(pert[i, v] - (-math.log(-math.log(u)))) < 1e-12
 
 
