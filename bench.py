@@ -193,12 +193,24 @@ def measure(cfg, K, W, dev):
     b_logp = logprob_bytes(cfg.n_positions, cfg.vocab, lb)
     b_step = b_attn + b_logp + append_bytes(cfg)
     kv_rotated = n_sets * 2 * wk.lens.sum() * cfg.n_kv_heads * cfg.head_dim * 2
+    # next-token sampling for one decode step (batch rows of the vocabulary); outside the timed step
+    rows = wk.sets[0]["actor"][:cfg.batch]
+    toks = torch.empty(cfg.batch, dtype=torch.int32, device=dev)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for it in range(3):
+        wk.rb.rlhf_sample_tokens(rows, toks, 1.0, cfg.seed, it)
+    e0.record()
+    for it in range(20):
+        wk.rb.rlhf_sample_tokens(rows, toks, 1.0, cfg.seed, 3 + it)
+    e1.record()
+    torch.cuda.synchronize()
+    sample_us = e0.elapsed_time(e1) / 20 * 1e3
     res = dict(
         wk=wk, n_sets=n_sets, t_total=t_total, b_step=b_step, b_attn=b_attn, b_logp=b_logp, lb=lb,
         ms_per_step=t_total / K * 1e3, value=b_step / (t_total / K) / 1e9,
         attn_gbps=b_attn / t_attn.mean() / 1e9, logp_gbps=b_logp / t_logp.mean() / 1e9,
         attn_us=t_attn.mean() * 1e6, logp_us=t_logp.mean() * 1e6, append_us=t_append.mean() * 1e6,
-        attn_cold=bool(kv_rotated > 512e6), stats=wk.rb.rlhf_kv_arena_stats(wk.sets[0]["arena"]))
+        sample_us=sample_us, attn_cold=bool(kv_rotated > 512e6), stats=wk.rb.rlhf_kv_arena_stats(wk.sets[0]["arena"]))
     return res
 
 
@@ -263,6 +275,8 @@ def main():
             "logprob_kl_GBps": round(m["logp_gbps"], 1),
             "logprob_kl_frac_of_peak": round(m["logp_gbps"] / HBM_PEAK_GBPS, 4),
             "logprob_kl_us": round(m["logp_us"], 2), "append_us": round(m["append_us"], 2),
+            "sample_tokens_us_per_decode_step": round(m["sample_us"], 2),
+            "sample_tokens_Gelem_per_s": round(cfg.batch * cfg.vocab / m["sample_us"] / 1e3, 1),
             "arena_reserved_bytes": stats["reserved_bytes"], "arena_allocated_bytes": stats["allocated_bytes"],
             "arena_driver_allocations_after_create": 0,
         },
@@ -297,7 +311,8 @@ def main():
                 "logprob_kl_tokens_per_s": round(c.n_positions / (o["logp_us"] * 1e-6), 1),
                 "logprob_kl_GBps": round(o["logp_gbps"], 1),
                 "logprob_kl_frac_of_peak": round(o["logp_gbps"] / HBM_PEAK_GBPS, 4),
-                "append_us": round(o["append_us"], 2), "step_GBps": round(o["value"], 1)})
+                "append_us": round(o["append_us"], 2), "sample_tokens_us": round(o["sample_us"], 2),
+                "step_GBps": round(o["value"], 1)})
             o["wk"].close()
             del o
             torch.cuda.empty_cache()

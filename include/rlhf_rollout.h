@@ -258,6 +258,26 @@ int rlhf_token_logprobs_kl_rewards(const void *actor_logits, const void *ref_log
                                    int64_t row_stride_elems, int32_t logits_dtype,
                                    const rlhf_reward_shaping *shaping, void *stream);
 
+/* ------------------------------------------------------------------------
+ * Next-token sampling in one pass over the logits (Section 2.1: "the actor
+ * generates responses"; this is the step between a decode step's logits and the
+ * append of the next token).
+ *     temperature > 0: tokens_out[i] = argmax_v ( logits[i,v]/T + G_iv ), with
+ *         G_iv = -ln(-ln u_iv): an exact draw from softmax(logits[i,:]/T)
+ *         (Gumbel-max).  u_iv = (k + 1/2) / 2^23 with k the top 23 bits of word
+ *         v%4 of Philox4x32-10( counter = (v/4, i, offset low, offset high),
+ *         key = (seed low, seed high) ).  No noise is read from memory; use a
+ *         new offset for every decode step.
+ *     temperature == 0: greedy argmax.
+ *   Ties go to the lowest index.  logp_out (dev [n_rows] or NULL) receives
+ *   log softmax(logits[i,:]/T)[token] (T = 1 for greedy).
+ *   logits      dev [n_rows][row_stride_elems], F32 / BF16 / F16
+ *   tokens_out  dev [n_rows] int32
+ * ------------------------------------------------------------------------ */
+int rlhf_sample_tokens(const void *logits, int32_t *tokens_out, float *logp_out, int64_t n_rows,
+                       int32_t vocab, int64_t row_stride_elems, int32_t logits_dtype, float temperature,
+                       uint64_t seed, uint64_t offset, void *stream);
+
 /* Text for the most recent failure on this thread ("" if none). */
 const char *rlhf_last_error_string(void);
 

@@ -27,7 +27,7 @@ EXPORTS = [
     "rlhf_kv_arena_append", "rlhf_kv_arena_free_seq", "rlhf_kv_arena_reset", "rlhf_kv_arena_stats",
     "rlhf_kv_arena_views", "rlhf_kv_arena_host_state", "rlhf_kv_arena_gather",
     "rlhf_decode_attention_workspace_bytes", "rlhf_decode_attention", "rlhf_token_logprobs_kl",
-    "rlhf_token_logprobs_kl_rewards",
+    "rlhf_token_logprobs_kl_rewards", "rlhf_sample_tokens",
     "rlhf_last_error_string", "rlhf_version",
 ]
 
@@ -102,6 +102,8 @@ def lib() -> ctypes.CDLL:
         L.rlhf_token_logprobs_kl.argtypes = [vp, vp, vp, vp, vp, i64, i32, i64, i32, vp]
         L.rlhf_token_logprobs_kl_rewards.argtypes = [vp, vp, vp, vp, vp, i64, i32, i64, i32,
                                                      P(RewardShaping), vp]
+        L.rlhf_sample_tokens.argtypes = [vp, vp, vp, i64, i32, i64, i32, ctypes.c_float, ctypes.c_uint64,
+                                         ctypes.c_uint64, vp]
         L.rlhf_last_error_string.restype = ctypes.c_char_p
         L.rlhf_last_error_string.argtypes = []
         L.rlhf_version.argtypes = []
@@ -284,6 +286,20 @@ def rlhf_token_logprobs_kl_rewards(actor_logits, ref_logits, tokens, logp_out, k
                                                 _ptr(logp_out), _ptr(kl_out), n_positions, vocab,
                                                 row_stride_elems, logits_dtype, ctypes.byref(sh),
                                                 _stream(stream)))
+
+
+def rlhf_sample_tokens(logits, tokens_out, temperature, seed, offset=0, logp_out=None, n_rows=None,
+                       vocab=None, row_stride_elems=0, logits_dtype=None, stream=None) -> None:
+    if n_rows is None:
+        n_rows = logits.shape[0]
+    if vocab is None:
+        vocab = logits.shape[1]
+        row_stride_elems = logits.stride(0)
+    if logits_dtype is None:
+        logits_dtype = dtype_code(logits.dtype)
+    _check(lib().rlhf_sample_tokens(_ptr(logits), _ptr(tokens_out), _ptr(logp_out), n_rows, vocab,
+                                    row_stride_elems, logits_dtype, temperature, seed, offset,
+                                    _stream(stream)))
 
 
 def rlhf_last_error_string() -> str:

@@ -52,10 +52,12 @@ __device__ __forceinline__ uint4 philox4x32_10(uint4 c, uint2 k)
 // Gumbel noise from one 32-bit word.
 __device__ __forceinline__ float gumbel(uint32_t word)
 {
-    const float w = ((float)(word >> 9) + 0.5f) * (1.0f / 8388608.0f);  // in (0,1), exact
-    // e = -ln(1 - w) is Exp(1); the uniform of the definition is u = 1 - w, also exact
-    const float series = w * (1.0f + w * (0.5f + w * (1.0f / 3.0f + w * 0.25f)));
-    const float e = w < 0.015625f ? series : -__logf(1.0f - w);
+    const float u = ((float)(word >> 9) + 0.5f) * (1.0f / 8388608.0f);  // in (0,1), exact
+    // e = -ln u is Exp(1).  Near u = 1 it is taken from the series of -ln(1 - c),
+    // c = 1 - u (exact), because a hardware log loses relative accuracy there.
+    const float c = 1.0f - u;
+    const float series = c * (1.0f + c * (0.5f + c * (1.0f / 3.0f + c * 0.25f)));
+    const float e = c < 0.015625f ? series : -__logf(u);
     return -__logf(e);
 }
 

@@ -366,3 +366,82 @@ def test_reward_shaping_matches_oracle(gu, oracle, cfg_index, n, penalty):
     rb.rlhf_token_logprobs_kl_rewards(actor, ref, d(tok), logp2, kl2, 0.15, penalty=penalty)
     torch.cuda.synchronize()
     assert torch.equal(logp2, logp) and torch.equal(kl2, kl)
+
+
+# ---------------------------------------------------------------- sampling ----
+def _check_sampling(gu, oracle, logits, temperature, seed, offset, vocab=None, stride=0):
+    """The sampled decision is an argmax of fp32 scores on the GPU and of fp64
+    scores in the oracle, so a near-tie may legitimately resolve differently: the
+    GPU's token must reach the oracle's maximum perturbed score within 1e-3, and
+    rows whose top two scores are further apart than that must agree exactly."""
+    n = logits.shape[0]
+    tok = torch.full((n,), -7, dtype=torch.int32, device=gu.DEV)
+    logp = torch.full((n,), float("nan"), dtype=torch.float32, device=gu.DEV)
+    if vocab is None:
+        rb.rlhf_sample_tokens(logits, tok, temperature, seed, offset, logp_out=logp)
+    else:
+        rb.rlhf_sample_tokens(logits, tok, temperature, seed, offset, logp_out=logp, n_rows=n, vocab=vocab,
+                              row_stride_elems=stride, logits_dtype=rb.dtype_code(logits.dtype))
+    torch.cuda.synchronize()
+    code = rb.dtype_code(logits.dtype)
+    et, el, pert = oracle.sample_tokens(wl.to_storage(logits), code, temperature, seed, offset, vocab=vocab,
+                                        return_perturbed=True)
+    got = tok.cpu().numpy()
+    V = pert.shape[1]
+    assert ((got >= 0) & (got < V)).all()
+    rows = np.arange(n)
+    top = pert.max(axis=1)
+    assert (pert[rows, got] >= top - 1e-3).all()
+    second = np.partition(pert, V - 2, axis=1)[:, V - 2] if V > 1 else top - 1
+    clear = top - second > 1e-3
+    assert (got[clear] == et[clear]).all()
+    agree = got == et
+    x = logits.double().cpu().numpy()[:, :V] * (1.0 / temperature if temperature > 0 else 1.0)
+    import scipy.special
+    ref_logp = scipy.special.log_softmax(x, axis=1)[rows, got]       # log-prob of the token the GPU chose
+    assert np.abs(logp.cpu().numpy() - ref_logp).max() <= LOGP_TOL
+    assert np.abs(el[agree] - ref_logp[agree]).max() <= 1e-9
+    return got, agree.mean(), clear.mean()
+
+
+@pytest.mark.parametrize("cfg_index,n", [(1, 48), (2, 32), (5, 128)])
+@pytest.mark.parametrize("temperature", [1.0, 0.7, 0.0])
+def test_sampling_matches_oracle(gu, oracle, cfg_index, n, temperature):
+    cfg = wl.config(cfg_index)
+    actor, _ = wl.logits(cfg, n_positions=n, device=gu.DEV)
+    got, agree, clear = _check_sampling(gu, oracle, actor, temperature, 0xC0FFEE1234, 17)
+    _say(f"sampling cfg{cfg_index} T={temperature}: identical tokens {agree:.3f}, clear rows {clear:.3f}")
+    assert agree >= 0.98
+    if temperature > 0:
+        got2, _, _ = _check_sampling(gu, oracle, actor, temperature, 0xC0FFEE1234, 18)
+        assert (got != got2).mean() > 0.5                     # a new offset gives a new draw
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
+@pytest.mark.parametrize("vocab,stride,offset_elems", [(1003, 1003, 0), (4099, 4104, 0), (5, 8, 0), (2048, 2048, 1),
+                                                        (1, 1, 0)])
+def test_sampling_ragged_vocab_strides_and_alignment(gu, oracle, dtype, vocab, stride, offset_elems):
+    tdt = wl.torch_dtype(dtype)
+    n = 12
+    g = torch.Generator(device=gu.DEV)
+    g.manual_seed(vocab * 17 + stride)
+    buf = (torch.randn(n * stride + 8, generator=g, device=gu.DEV) * 3).to(tdt)
+    logits = buf[offset_elems:offset_elems + n * stride].view(n, stride)
+    for T in (0.0, 1.3):
+        _check_sampling(gu, oracle, logits, T, 5, 2 ** 33 + 9, vocab=vocab, stride=stride)
+
+
+def test_sampling_frequencies_on_the_gpu_follow_softmax(gu):
+    """Property that needs no oracle: the empirical distribution of many draws
+    from one fixed row is softmax(logits / T)."""
+    import scipy.special
+    import scipy.stats
+    logits = torch.tensor([0.0, 1.0, -1.0, 2.5, 0.3, -3.0, 0.9, -0.2], device=gu.DEV)
+    N, T = 80000, 0.8
+    tok = torch.empty(N, dtype=torch.int32, device=gu.DEV)
+    rb.rlhf_sample_tokens(logits.repeat(N, 1).contiguous(), tok, T, 4242, 1)
+    torch.cuda.synchronize()
+    p = scipy.special.softmax(logits.double().cpu().numpy() / T)
+    counts = np.bincount(tok.cpu().numpy(), minlength=8)
+    chi2 = ((counts - N * p) ** 2 / (N * p)).sum()
+    assert chi2 < scipy.stats.chi2.ppf(1 - 1e-6, 7), chi2
