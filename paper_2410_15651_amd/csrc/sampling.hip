@@ -17,7 +17,7 @@
 // u is within 2^-6 of 1 (where a hardware log loses relative accuracy and where
 // the largest Gumbel values, the ones that decide the argmax, come from).
 //
-// One workgroup of 256 lanes owns one row.  The pass is bound by the vector
+// One workgroup (256 or 1024 lanes) owns one row.  The pass is bound by the vector
 // ALU (ten Philox rounds per four logits plus three transcendentals per
 // logit), not by HBM: a decode step reads only batch x vocab logits.
 #include <hip/hip_runtime.h>
@@ -30,8 +30,9 @@
 namespace rlhf {
 namespace {
 
-constexpr int kThreads = 256;
-constexpr int kWaves = kThreads / 64;
+// Lanes per row: 256 when there are rows enough to fill the chip, 1024 when a
+// decode step brings only a few hundred rows (then a row's latency matters).
+constexpr int kFewRows = 1024;
 constexpr float kLift = 40.0f;
 constexpr float kNoRef = -1.0e30f;
 
@@ -120,11 +121,12 @@ __device__ __forceinline__ void better(float &z, int &i, float oz, int oi)
     }
 }
 
-template <int DT, bool VEC, bool NOISE>
+template <int DT, bool VEC, bool NOISE, int kThreads>
 __global__ __launch_bounds__(kThreads) void sample_tokens_kernel(
     const void *__restrict__ logits, int32_t *__restrict__ tokens_out, float *__restrict__ logp_out,
     int vocab, int64_t stride, float inv_t, uint2 key, uint2 off)
 {
+    constexpr int kWaves = kThreads / 64;
     __shared__ float s_f[kWaves];
     __shared__ int s_i[kWaves];
     const int64_t row64 = blockIdx.x;
@@ -210,22 +212,31 @@ template <int DT>
 int launch(const void *logits, int32_t *tokens, float *logp, int64_t n, int vocab, int64_t stride, bool vec,
            float temperature, uint64_t seed, uint64_t offset, hipStream_t s)
 {
-    const dim3 grid((unsigned)n), block(kThreads);
+    const dim3 grid((unsigned)n);
     const uint2 key = make_uint2((uint32_t)seed, (uint32_t)(seed >> 32));
     const uint2 off = make_uint2((uint32_t)offset, (uint32_t)(offset >> 32));
     const bool noise = temperature > 0.f;
+    const bool wide = n < kFewRows;
     const float inv_t = noise ? 1.0f / temperature : 1.0f;
-#define RLHF_SAMPLE_LAUNCH(V, N)                                                                        \
-    hipLaunchKernelGGL((sample_tokens_kernel<DT, V, N>), grid, block, 0, s, logits, tokens, logp, vocab, \
+#define RLHF_SAMPLE_LAUNCH(V, N, T)                                                                       \
+    hipLaunchKernelGGL((sample_tokens_kernel<DT, V, N, T>), grid, dim3(T), 0, s, logits, tokens, logp, vocab, \
                        stride, inv_t, key, off)
+#define RLHF_SAMPLE_PICK(V, N)          \
+    do {                                \
+        if (wide)                       \
+            RLHF_SAMPLE_LAUNCH(V, N, 1024); \
+        else                            \
+            RLHF_SAMPLE_LAUNCH(V, N, 256);  \
+    } while (0)
     if (vec && noise)
-        RLHF_SAMPLE_LAUNCH(true, true);
+        RLHF_SAMPLE_PICK(true, true);
     else if (vec)
-        RLHF_SAMPLE_LAUNCH(true, false);
+        RLHF_SAMPLE_PICK(true, false);
     else if (noise)
-        RLHF_SAMPLE_LAUNCH(false, true);
+        RLHF_SAMPLE_PICK(false, true);
     else
-        RLHF_SAMPLE_LAUNCH(false, false);
+        RLHF_SAMPLE_PICK(false, false);
+#undef RLHF_SAMPLE_PICK
 #undef RLHF_SAMPLE_LAUNCH
     RLHF_LAUNCH_CHECK("sample_tokens_kernel");
     return RLHF_OK;

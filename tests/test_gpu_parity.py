@@ -404,7 +404,7 @@ def _check_sampling(gu, oracle, logits, temperature, seed, offset, vocab=None, s
     return got, agree.mean(), clear.mean()
 
 
-@pytest.mark.parametrize("cfg_index,n", [(1, 48), (2, 32), (5, 128)])
+@pytest.mark.parametrize("cfg_index,n", [(1, 48), (2, 32), (5, 128), (3, 1100)])   # 1100 rows: the 256-lane variant
 @pytest.mark.parametrize("temperature", [1.0, 0.7, 0.0])
 def test_sampling_matches_oracle(gu, oracle, cfg_index, n, temperature):
     cfg = wl.config(cfg_index)
