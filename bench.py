@@ -33,11 +33,11 @@ METRIC = "decode-attn HBM GB/s (% of MI355X peak) + logprob/KL tokens/sec, 1 GPU
 # only while the kernel sources still hash to the value recorded with them.
 PMC_TRAFFIC = {
     "logprob_kl": {"sources": ["logprob_kl.hip", "device_ops.h"],
-                   "sha256": "74881942a0a0ba2ce6083f227752f09b957d0284ddd4433724795e97d0fc4a8f",
-                   "bytes": 67249726834 + 9066664},
+                   "sha256": "deef495df77db1122d46065078daa6de157d2779e3dd3efc06e8985e2b872b76",
+                   "bytes": 67248646305 + 8854864},
     "decode_attn": {"sources": ["attention.hip", "device_ops.h"],
-                    "sha256": "7a4496821e3ef1d9f1f80c7dad9fb17a41be8080552a689ad18a39e7a18f5333",
-                    "bytes": 1605456389 + 12761448 + 13416415 + 2097152},
+                    "sha256": "5bd47e18145ad137845588b26f598a394a634db6a42112262be155b25d932de0",
+                    "bytes": 1605410299 + 12763824 + 13416133 + 2097152},
 }
 
 
