@@ -70,6 +70,12 @@ class OracleLib:
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
             ctypes.c_void_p, ctypes.c_void_p,
             ctypes.c_int64, ctypes.c_int, ctypes.c_int64, ctypes.c_int, ctypes.c_double, ctypes.c_int]
+        lib.oracle_prefill_attention.restype = ctypes.c_int
+        lib.oracle_prefill_attention.argtypes = [
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+            ctypes.c_int, ctypes.c_double]
         lib.oracle_philox4x32_10.restype = None
         lib.oracle_philox4x32_10.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
         lib.oracle_sample_tokens.restype = ctypes.c_int
@@ -156,6 +162,37 @@ class OracleLib:
         return ref_logp, reward
 
 
+    def prefill_attention(self, q, cu_q, k_pages, v_pages, page_table, seq_lens, dtype, scale=None):
+        """q [T,Hq,D] packed query rows, cu_q [B+1] int32 offsets (sequence b owns rows
+        cu_q[b]:cu_q[b+1], the last tokens of its cache) -> out [T,Hq,D] float64."""
+        q = _storage(q, dtype)
+        k_pages = _storage(k_pages, dtype)
+        v_pages = _storage(v_pages, dtype)
+        T, Hq, D = q.shape
+        n_pages, Hkv, P, D2 = k_pages.shape
+        assert D2 == D and v_pages.shape == k_pages.shape
+        cu_q = np.ascontiguousarray(cu_q, dtype=np.int32)
+        B = cu_q.shape[0] - 1
+        assert cu_q[0] == 0 and cu_q[-1] == T
+        page_table = np.ascontiguousarray(page_table, dtype=np.int32).reshape(B, -1)
+        seq_lens = np.ascontiguousarray(seq_lens, dtype=np.int32)
+        assert seq_lens.shape == (B,)
+        used = (seq_lens.astype(np.int64) + P - 1) // P
+        for b in range(B):
+            row = page_table[b, :used[b]]
+            if row.size and (row.min() < 0 or row.max() >= n_pages):
+                raise ValueError("page table entry out of range")
+        if scale is None:
+            scale = 1.0 / np.sqrt(D)
+        out = np.zeros((T, Hq, D), dtype=np.float64)
+        rc = self._lib.oracle_prefill_attention(
+            q.ctypes.data, cu_q.ctypes.data, k_pages.ctypes.data, v_pages.ctypes.data,
+            page_table.ctypes.data, seq_lens.ctypes.data, out.ctypes.data,
+            B, Hq, Hkv, D, P, page_table.shape[1], dtype, float(scale))
+        if rc != 0:
+            raise ValueError("oracle_prefill_attention rejected its arguments")
+        return out
+
     def philox4x32_10(self, ctr, key):
         c = np.ascontiguousarray(ctr, dtype=np.uint32)
         k = np.ascontiguousarray(key, dtype=np.uint32)
@@ -207,6 +244,10 @@ def token_logprobs_kl(*args, **kw):
 
 def token_rewards(*args, **kw):
     return _load().token_rewards(*args, **kw)
+
+
+def prefill_attention(*args, **kw):
+    return _load().prefill_attention(*args, **kw)
 
 
 def philox4x32_10(*args, **kw):

@@ -20,6 +20,8 @@
  *                             the whole vocabulary
  *   oracle_token_rewards      the reference model's log-probability of the
  *                             token and the KL-penalised per-token reward
+ *   oracle_prefill_attention  causal attention of a block of new tokens per
+ *                             sequence over the same paged cache
  *   oracle_sample_tokens      next-token sampling from softmax(logits / T) by
  *                             Gumbel-max over counter-based (Philox) uniforms
  *
@@ -381,6 +383,78 @@ int oracle_sample_tokens(const void *logits, int32_t *tokens, double *logp, doub
             s += exp(load_elem(logits, base + v, dtype) * inv_t - m);
         tokens[i] = best;
         logp[i] = load_elem(logits, base + (size_t)best, dtype) * inv_t - (m + log(s));
+    }
+    return 0;
+}
+
+/*
+ * Causal attention for a block of new tokens per sequence ("prefill": the
+ * prompt, or a chunk of it, entering the cache before generation starts;
+ * Section 2.1, "the actor generates responses to prompts").  The keys and
+ * values of the new tokens are already in the paged cache.  Sequence b brings
+ * n_b = cu_q[b+1] - cu_q[b] query rows; they are the LAST n_b tokens of its
+ * L_b = seq_lens[b] cached tokens, so query row i sits at logical position
+ * p = L_b - n_b + i and attends to keys 0 .. p (itself included):
+ *   s_j = scale * <q_i, K_j>,  out_i = sum_{j<=p} softmax(s)_j V_j .
+ *
+ *   q    [cu_q[B]][Hq][D] packed rows, storage dtype
+ *   out  [cu_q[B]][Hq][D] double
+ * Pages, page table and head mapping as in oracle_decode_attention.
+ */
+int oracle_prefill_attention(const void *q, const int32_t *cu_q, const void *k_pages, const void *v_pages,
+                             const int32_t *page_table, const int32_t *seq_lens, double *out,
+                             int B, int Hq, int Hkv, int D, int P, int max_pages, int dtype, double scale)
+{
+    if (!q || !cu_q || !k_pages || !v_pages || !page_table || !seq_lens || !out)
+        return -1;
+    if (B < 0 || Hq <= 0 || Hkv <= 0 || D <= 0 || P <= 0 || max_pages < 0 || Hq % Hkv)
+        return -1;
+    const int G = Hq / Hkv;
+    const size_t page_elems = (size_t)Hkv * P * D;
+    for (int b = 0; b < B; ++b) {
+        const int n = cu_q[b + 1] - cu_q[b];
+        if (n < 0 || n > seq_lens[b] || seq_lens[b] > max_pages * P)
+            return -1;
+    }
+    for (int b = 0; b < B; ++b) {
+        const int n = cu_q[b + 1] - cu_q[b];
+        const int first = seq_lens[b] - n;
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+        for (int i = 0; i < n; ++i) {
+            for (int hq = 0; hq < Hq; ++hq) {
+                const int p = first + i;          /* last key this query may see */
+                const int hkv = hq / G;
+                const size_t qbase = (((size_t)cu_q[b] + i) * Hq + hq) * D;
+                double *o = out + qbase;
+                double m = -INFINITY;
+                for (int j = 0; j <= p; ++j) {
+                    const size_t page = (size_t)page_table[(size_t)b * max_pages + j / P];
+                    const size_t row = page * page_elems + ((size_t)hkv * P + j % P) * D;
+                    double s = 0.0;
+                    for (int d = 0; d < D; ++d)
+                        s += load_elem(q, qbase + d, dtype) * load_elem(k_pages, row + d, dtype);
+                    s *= scale;
+                    if (s > m)
+                        m = s;
+                }
+                double denom = 0.0;
+                for (int d = 0; d < D; ++d)
+                    o[d] = 0.0;
+                for (int j = 0; j <= p; ++j) {
+                    const size_t page = (size_t)page_table[(size_t)b * max_pages + j / P];
+                    const size_t row = page * page_elems + ((size_t)hkv * P + j % P) * D;
+                    double s = 0.0;
+                    for (int d = 0; d < D; ++d)
+                        s += load_elem(q, qbase + d, dtype) * load_elem(k_pages, row + d, dtype);
+                    const double w = exp(s * scale - m);
+                    denom += w;
+                    for (int d = 0; d < D; ++d)
+                        o[d] += w * load_elem(v_pages, row + d, dtype);
+                }
+                for (int d = 0; d < D; ++d)
+                    o[d] /= denom;
+            }
+        }
     }
     return 0;
 }

@@ -1,7 +1,7 @@
 """Are the oracle's pins strong enough?  Each case plants one plausible mistake
 in a copy of the oracle's C source (on the CPU, in a temporary directory),
 builds it, and runs the pin tests of test_oracle_attention.py,
-test_oracle_logprob_kl.py and test_oracle_sampling.py against the copy.  Every planted mistake must make at
+test_oracle_logprob_kl.py, test_oracle_sampling.py and test_oracle_prefill.py against the copy.  Every planted mistake must make at
 least one pin fail; the unmodified source must pass them all."""
 import inspect
 import os
@@ -11,6 +11,7 @@ import pytest
 import oracle as oracle_pkg
 import test_oracle_attention as pins_attention
 import test_oracle_logprob_kl as pins_logprob
+import test_oracle_prefill as pins_prefill
 import test_oracle_sampling as pins_sampling
 
 SRC = os.path.join(os.path.dirname(oracle_pkg.__file__), "rollout_oracle.c")
@@ -100,6 +101,15 @@ MUTANTS = [
      "sampling"),
     ("sampling: logp without the temperature", "s += exp(load_elem(logits, base + v, dtype) * inv_t - m);",
      "s += exp(load_elem(logits, base + v, dtype) - m);", "sampling"),
+    ("prefill: query cannot see itself", "                for (int j = 0; j <= p; ++j) {\n                    const size_t page = (size_t)page_table[(size_t)b * max_pages + j / P];\n                    const size_t row = page * page_elems + ((size_t)hkv * P + j % P) * D;\n                    double s = 0.0;\n                    for (int d = 0; d < D; ++d)\n                        s += load_elem(q, qbase + d, dtype) * load_elem(k_pages, row + d, dtype);\n                    const double w",
+     "                for (int j = 0; j < p + (p == 0); ++j) {\n                    const size_t page = (size_t)page_table[(size_t)b * max_pages + j / P];\n                    const size_t row = page * page_elems + ((size_t)hkv * P + j % P) * D;\n                    double s = 0.0;\n                    for (int d = 0; d < D; ++d)\n                        s += load_elem(q, qbase + d, dtype) * load_elem(k_pages, row + d, dtype);\n                    const double w", "prefill"),
+    ("prefill: no causal mask", "const int p = first + i;          /* last key this query may see */",
+     "const int p = seq_lens[b] - 1 + 0 * (first + i);", "prefill"),
+    ("prefill: block placed at the start of the cache", "const int first = seq_lens[b] - n;\n#pragma omp",
+     "const int first = 0 * (seq_lens[b] - n);\n#pragma omp", "prefill"),
+    ("prefill: wrong head group", "const int p = first + i;          /* last key this query may see */\n                const int hkv = hq / G;",
+     "const int p = first + i;          /* last key this query may see */\n                const int hkv = hq % Hkv;", "prefill"),
+    ("prefill: scale dropped", "const double w = exp(s * scale - m);", "const double w = exp(s - m);", "prefill"),
     ("padding: not zeroed", "            logp[i] = 0.0;\n            kl[i] = 0.0;\n            continue;",
      "            logp[i] = -1.0;\n            kl[i] = 0.0;\n            continue;", "logprob"),
 ]
@@ -107,7 +117,8 @@ MUTANTS = [
 
 def _pins(which):
     mods = {"attention": [pins_attention], "logprob": [pins_logprob], "sampling": [pins_sampling],
-            "both": [pins_attention, pins_logprob], "all": [pins_attention, pins_logprob, pins_sampling]}[which]
+            "prefill": [pins_prefill],
+            "both": [pins_attention, pins_logprob], "all": [pins_attention, pins_logprob, pins_sampling, pins_prefill]}[which]
     out = []
     for mod in mods:
         for name, fn in sorted(vars(mod).items()):
