@@ -278,6 +278,34 @@ int rlhf_sample_tokens(const void *logits, int32_t *tokens_out, float *logp_out,
                        int32_t vocab, int64_t row_stride_elems, int32_t logits_dtype, float temperature,
                        uint64_t seed, uint64_t offset, void *stream);
 
+/* ------------------------------------------------------------------------
+ * Prefill attention (Section 2.1: generation starts from the prompts; this is
+ * the step that brings a prompt, or a chunk of it, into the cache before the
+ * one-token-per-step loop).  The new tokens' K/V rows have been appended to the
+ * arena already (rlhf_kv_arena_append takes any number of tokens per
+ * sequence).  Sequence b brings n_b = cu_q[b+1] - cu_q[b] query rows, the last
+ * n_b of its L_b = seq_lens[b] cached tokens; row i sits at position
+ * p = L_b - n_b + i and attends causally to keys 0 .. p:
+ *     s_j = softmax_scale * <q_i[h,:], K_j>,  out_i[h,:] = sum_{j<=p} softmax(s)_j V_j
+ * with kv head h / (n_q_heads / n_kv_heads).  Matrix-core products, fp32
+ * accumulation, one pass with a running softmax reference.
+ *
+ *   params     shapes as for decode attention (max_seq_len: as there)
+ *   q          dev [cu_q[batch]][n_q_heads][head_dim], qkv_dtype, rows packed
+ *              sequence after sequence
+ *   cu_q       dev [batch+1] int32, non-decreasing, cu_q[0] = 0
+ *   max_q_len  host: an upper bound on n_b.  It sizes the launch; rows of a
+ *              sequence at or beyond max_q_len are NOT computed.
+ *   out        dev, same shape as q, out_dtype
+ * A sequence with n_b = 0 is skipped; one with n_b > L_b (more query rows than
+ * cached tokens) is skipped too and its rows of out are left untouched.
+ * q, k_arena, v_arena and out must be 16-byte aligned.  n_q_heads / n_kv_heads
+ * may not exceed 256 (RLHF_ERR_UNSUPPORTED).
+ * ------------------------------------------------------------------------ */
+int rlhf_prefill_attention(const rlhf_attn_params *params, const void *q, const int32_t *cu_q,
+                           int32_t max_q_len, const void *k_arena, const void *v_arena,
+                           const int32_t *page_table, const int32_t *seq_lens, void *out, void *stream);
+
 /* Text for the most recent failure on this thread ("" if none). */
 const char *rlhf_last_error_string(void);
 

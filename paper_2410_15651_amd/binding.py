@@ -27,7 +27,7 @@ EXPORTS = [
     "rlhf_kv_arena_append", "rlhf_kv_arena_free_seq", "rlhf_kv_arena_reset", "rlhf_kv_arena_stats",
     "rlhf_kv_arena_views", "rlhf_kv_arena_host_state", "rlhf_kv_arena_gather",
     "rlhf_decode_attention_workspace_bytes", "rlhf_decode_attention", "rlhf_token_logprobs_kl",
-    "rlhf_token_logprobs_kl_rewards", "rlhf_sample_tokens",
+    "rlhf_token_logprobs_kl_rewards", "rlhf_sample_tokens", "rlhf_prefill_attention",
     "rlhf_last_error_string", "rlhf_version",
 ]
 
@@ -104,6 +104,7 @@ def lib() -> ctypes.CDLL:
                                                      P(RewardShaping), vp]
         L.rlhf_sample_tokens.argtypes = [vp, vp, vp, i64, i32, i64, i32, ctypes.c_float, ctypes.c_uint64,
                                          ctypes.c_uint64, vp]
+        L.rlhf_prefill_attention.argtypes = [P(AttnParams), vp, vp, i32, vp, vp, vp, vp, vp, vp]
         L.rlhf_last_error_string.restype = ctypes.c_char_p
         L.rlhf_last_error_string.argtypes = []
         L.rlhf_version.argtypes = []
@@ -253,6 +254,13 @@ def rlhf_decode_attention(params: AttnParams, q, k_arena, v_arena, page_table, s
     _check(lib().rlhf_decode_attention(ctypes.byref(params), _ptr(q), _ptr(k_arena), _ptr(v_arena),
                                        _ptr(page_table), _ptr(seq_lens), _ptr(out), _ptr(workspace),
                                        workspace_bytes, _stream(stream)))
+
+
+def rlhf_prefill_attention(params: AttnParams, q, cu_q, max_q_len: int, k_arena, v_arena, page_table,
+                           seq_lens, out, stream=None) -> None:
+    _check(lib().rlhf_prefill_attention(ctypes.byref(params), _ptr(q), _ptr(cu_q), int(max_q_len),
+                                        _ptr(k_arena), _ptr(v_arena), _ptr(page_table), _ptr(seq_lens),
+                                        _ptr(out), _stream(stream)))
 
 
 # ----------------------------------------------------------- logprob/KL ----

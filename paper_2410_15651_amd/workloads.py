@@ -159,6 +159,23 @@ def qkv(cfg: RolloutConfig, lens: np.ndarray, device="cpu", seed: Optional[int] 
     return q, ks, vs
 
 
+def prompt_lengths(cfg: RolloutConfig, seed: Optional[int] = None) -> np.ndarray:
+    """Prompt lengths for the prefill step: uniform integers on [len_lo/2,
+    len_hi/2] (at least 1) -- the prompt as half of the final cache, the other
+    half being generated.  int32 [batch]."""
+    rng = _cpu_rng(cfg.seed if seed is None else seed, 6)
+    lo, hi = max(1, cfg.len_lo // 2), max(1, cfg.len_hi // 2)
+    return rng.integers(lo, hi + 1, size=cfg.batch, dtype=np.int64).astype(np.int32)
+
+
+def query_rows(cfg: RolloutConfig, n_rows: int, device="cpu", seed: Optional[int] = None) -> torch.Tensor:
+    """Packed query rows [n_rows, Hq, D] in the cache dtype, N(0, qkv_std^2)."""
+    seed = cfg.seed if seed is None else seed
+    g = _device_gen(device, seed, 7)
+    q = torch.randn(n_rows, cfg.n_q_heads, cfg.head_dim, generator=g, device=device, dtype=torch.float32)
+    return (q * cfg.qkv_std).to(torch_dtype(cfg.kv_dtype))
+
+
 def tokens(cfg: RolloutConfig, n_positions: Optional[int] = None, seed: Optional[int] = None
            ) -> np.ndarray:
     """Sampled token ids, uniform over the vocabulary, int32 [n_positions]."""

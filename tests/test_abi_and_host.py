@@ -25,7 +25,7 @@ def _declared_functions():
 
 def test_library_exports_every_declared_function():
     names = _declared_functions()
-    assert len(names) >= 17
+    assert len(names) >= 18
     L = ctypes.CDLL(rb.LIB_PATH)
     for n in names:
         assert hasattr(L, n), n
@@ -140,6 +140,13 @@ def test_compute_entry_points_validate_before_launching():
     assert rb.rlhf_decode_attention_workspace_bytes(p) >= 2 * 4 * (64 + 2) * 4
     with pytest.raises(rb.RlhfError) as e:                       # NULL buffers
         rb.rlhf_decode_attention(p, 0, 0, 0, 0, 0, 0, 0, 0)
+    assert e.value.status == rb.RLHF_ERR_INVALID
+    with pytest.raises(rb.RlhfError) as e:                       # NULL buffers
+        rb.rlhf_prefill_attention(p, 0, 0, 8, 0, 0, 0, 0, 0)
+    assert e.value.status == rb.RLHF_ERR_INVALID
+    rb.rlhf_prefill_attention(p, 0, 0, 0, 0, 0, 0, 0, 0)         # no rows: nothing to do
+    with pytest.raises(rb.RlhfError) as e:
+        rb.rlhf_prefill_attention(rb.attn_params(2, 4, 3, 64, 4, rb.RLHF_BF16), 16, 16, 8, 16, 16, 16, 16, 16)
     assert e.value.status == rb.RLHF_ERR_INVALID
     with pytest.raises(rb.RlhfError) as e:
         rb.rlhf_token_logprobs_kl(0, 0, 0, 0, 0, n_positions=4, vocab=10, logits_dtype=rb.RLHF_F32)

@@ -1,0 +1,211 @@
+"""GPU parity of the prefill (causal block) attention, called through the C ABI,
+against the fp64 CPU oracle on the same seeded inputs: 2e-3 max-abs, the
+attention tolerance."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2410_15651_amd import binding as rb
+from paper_2410_15651_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+ATTN_TOL = 2e-3
+P = wl.PAGE_TOKENS
+
+
+@pytest.fixture(scope="module")
+def gu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import gpu_util
+    return gpu_util
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _run(gu, cfg, A, q, cu, max_q_len, out_dtype=None, scale=0.0, max_seq_len=0):
+    k, v, table, lens = A.views()
+    params = rb.attn_params(cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, A.mpps,
+                            wl.DTYPE_CODE[cfg.kv_dtype], out_dtype=out_dtype, softmax_scale=scale,
+                            max_seq_len=max_seq_len)
+    odt = torch.float32 if out_dtype == rb.RLHF_F32 else wl.torch_dtype(cfg.kv_dtype)
+    out = torch.full(tuple(q.shape), float("nan"), dtype=odt, device=gu.DEV)
+    cu_d = torch.from_numpy(cu).to(gu.DEV)
+    rb.rlhf_prefill_attention(params, q, cu_d, max_q_len, k, v, table, lens, out)
+    torch.cuda.synchronize()
+    return out
+
+
+def _oracle(oracle, cfg, q, cu, ks, vs, table, lens, n_pages, scale=None):
+    kp, vp = wl.plain_pages([wl.to_storage(k) for k in ks], [wl.to_storage(v) for v in vs], table, n_pages)
+    return oracle.prefill_attention(wl.to_storage(q), cu, kp, vp, table, lens, wl.DTYPE_CODE[cfg.kv_dtype],
+                                    scale=scale)
+
+
+def _rows(cfg, lens, how):
+    """New rows per sequence: the whole cache ('full'), a trailing chunk
+    ('chunk'), or a mix with an empty and a one-row sequence ('mix')."""
+    rng = np.random.default_rng(cfg.seed + 77)
+    if how == "full":
+        n = lens.copy()
+    elif how == "chunk":
+        n = np.array([int(rng.integers(1, L + 1)) for L in lens], dtype=np.int32)
+    else:
+        n = lens.copy()
+        n[0] = 0
+        n[-1] = 1
+        if len(n) > 2:
+            n[1] = min(int(lens[1]), 17)
+    return n.astype(np.int32)
+
+
+SMALL = [
+    # (config index, overrides, rows) -- several position blocks, pages and a ragged tail
+    (1, dict(batch=3, len_lo=1, len_hi=300), "full"),                                  # f16 MHA, D=64
+    (2, dict(batch=2, n_q_heads=4, n_kv_heads=4, len_lo=200, len_hi=600), "full"),     # bf16 MHA, D=64: 3 blocks
+    (3, dict(batch=2, n_q_heads=4, n_kv_heads=4, len_lo=100, len_hi=700), "chunk"),    # D=128
+    (5, dict(batch=3, n_q_heads=16, n_kv_heads=2, len_lo=20, len_hi=260), "full"),     # group of 8
+    (5, dict(batch=3, n_q_heads=16, n_kv_heads=2, len_lo=20, len_hi=400), "mix"),
+    (4, dict(batch=2, n_q_heads=6, n_kv_heads=2, len_lo=90, len_hi=200), "full"),      # group of 3: idle columns
+    (3, dict(batch=2, n_q_heads=48, n_kv_heads=2, len_lo=30, len_hi=120), "chunk"),    # group of 24
+    (1, dict(batch=2, n_q_heads=32, n_kv_heads=2, head_dim=128, len_lo=33, len_hi=90), "full"),   # f16, group of 16
+    (5, dict(batch=2, n_q_heads=8, n_kv_heads=2, head_dim=64, len_lo=1, len_hi=50), "full"),
+]
+
+
+@pytest.mark.parametrize("cfg_index,over,how", SMALL)
+def test_prefill_matches_oracle(gu, oracle, cfg_index, over, how):
+    cfg = wl.small_variant(wl.config(cfg_index), **over)
+    lens = wl.seq_lengths(cfg)
+    n_new = _rows(cfg, lens, how)
+    cu = np.concatenate([[0], np.cumsum(n_new)]).astype(np.int32)
+    _say(f"prefill cfg{cfg_index} {over} lens={lens.tolist()} rows={n_new.tolist()}")
+    _, ks, vs = wl.qkv(cfg, lens, device=gu.DEV)
+    q = wl.query_rows(cfg, int(cu[-1]), device=gu.DEV)
+    A = gu.FilledArena(cfg, lens, ks, vs)
+    try:
+        table, _, _ = A.host_state()
+        expect = _oracle(oracle, cfg, q, cu, ks, vs, table, lens, A.n_pages)
+        out32 = _run(gu, cfg, A, q, cu, int(n_new.max()), out_dtype=rb.RLHF_F32)
+        assert torch.isfinite(out32).all()
+        err32 = np.abs(out32.cpu().numpy().astype(np.float64) - expect).max()
+        out16 = _run(gu, cfg, A, q, cu, int(n_new.max()) + 5)
+        err16 = np.abs(out16.float().cpu().numpy().astype(np.float64) - expect).max()
+        ulp = np.abs(expect).max() * (2.0 ** -8 if cfg.kv_dtype == "bf16" else 2.0 ** -11)
+        _say(f"  max-abs err: f32 out {err32:.3e}, {cfg.kv_dtype} out {err16:.3e}")
+        assert err32 <= ATTN_TOL
+        assert err16 <= ATTN_TOL + ulp        # plus half an ulp of the 16-bit output itself
+    finally:
+        A.close()
+
+
+def test_prefill_first_row_is_its_value_row_and_skipped_sequences_stay_untouched(gu, oracle):
+    cfg = wl.small_variant(wl.config(3), batch=4, n_q_heads=4, n_kv_heads=2, len_lo=0, len_hi=64)
+    lens = np.array([40, 16, 1, 33], dtype=np.int32)
+    n_new = np.array([40, 17, 1, 2], dtype=np.int32)        # sequence 1 claims more rows than it has tokens
+    cu = np.concatenate([[0], np.cumsum(n_new)]).astype(np.int32)
+    _, ks, vs = wl.qkv(cfg, lens, device=gu.DEV)
+    q = wl.query_rows(cfg, int(cu[-1]), device=gu.DEV)
+    A = gu.FilledArena(cfg, lens, ks, vs)
+    try:
+        out = _run(gu, cfg, A, q, cu, 40, out_dtype=rb.RLHF_F32)
+        assert torch.isnan(out[cu[1]:cu[2]]).all()                       # skipped, as documented
+        for h in range(4):                                              # position 0 sees one key: exactly V_0
+            assert torch.equal(out[0, h], vs[0][0, h // 2].float())
+            assert torch.equal(out[cu[2], h], vs[2][0, h // 2].float())
+        keep = [0, 2, 3]
+        table, _, _ = A.host_state()
+        cu_k = np.concatenate([[0], np.cumsum(n_new[keep])]).astype(np.int32)
+        qk = torch.cat([q[cu[b]:cu[b + 1]] for b in keep])
+        expect = _oracle(oracle, cfg, qk, cu_k, [ks[b] for b in keep], [vs[b] for b in keep], table[keep],
+                         lens[keep], A.n_pages)
+        got = torch.cat([out[cu[b]:cu[b + 1]] for b in keep]).cpu().numpy().astype(np.float64)
+        assert np.abs(got - expect).max() <= ATTN_TOL
+        # explicit softmax scale, and a launch bound below the longest block: rows beyond it are not computed
+        expect_s = _oracle(oracle, cfg, qk, cu_k, [ks[b] for b in keep], [vs[b] for b in keep], table[keep],
+                           lens[keep], A.n_pages, scale=0.31)
+        out_s = _run(gu, cfg, A, q, cu, 40, out_dtype=rb.RLHF_F32, scale=0.31)
+        got_s = torch.cat([out_s[cu[b]:cu[b + 1]] for b in keep]).cpu().numpy().astype(np.float64)
+        assert np.abs(got_s - expect_s).max() <= ATTN_TOL
+        assert np.abs(expect_s - expect).max() > 10 * ATTN_TOL
+    finally:
+        A.close()
+
+
+def test_prefill_rows_equal_decode_steps(gu):
+    """A prefill row at position p and a decode step over the first p+1 tokens
+    are the same computation: the two kernels must agree to rounding."""
+    cfg = wl.small_variant(wl.config(5), batch=2, n_q_heads=16, n_kv_heads=2, len_lo=150, len_hi=300)
+    lens = wl.seq_lengths(cfg)
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    _, ks, vs = wl.qkv(cfg, lens, device=gu.DEV)
+    q = wl.query_rows(cfg, int(cu[-1]), device=gu.DEV)
+    A = gu.FilledArena(cfg, lens, ks, vs)
+    try:
+        out = _run(gu, cfg, A, q, cu, int(lens.max()), out_dtype=rb.RLHF_F32)
+        last = torch.stack([q[cu[b + 1] - 1] for b in range(cfg.batch)]).contiguous()
+        dec = gu.run_attention(cfg, A, last, out_dtype=rb.RLHF_F32)
+        for b in range(cfg.batch):
+            assert (out[cu[b + 1] - 1] - dec[b]).abs().max().item() <= 1e-5
+    finally:
+        A.close()
+
+
+def test_prefill_is_bit_identical_under_page_permutation(gu):
+    base = wl.small_variant(wl.config(3), batch=3, n_q_heads=8, n_kv_heads=4, len_lo=100, len_hi=500)
+    lens = wl.seq_lengths(base)
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    _, ks, vs = wl.qkv(base, lens, device=gu.DEV)
+    q = wl.query_rows(base, int(cu[-1]), device=gu.DEV)
+    outs = []
+    for shuffled in (False, True):
+        cfg = wl.small_variant(base, shuffled_pages=shuffled)
+        A = gu.FilledArena(cfg, lens, ks, vs, slack_pages=11)
+        try:
+            outs.append(_run(gu, cfg, A, q, cu, int(lens.max()), out_dtype=rb.RLHF_F32))
+        finally:
+            A.close()
+    assert torch.equal(outs[0].view(torch.int32), outs[1].view(torch.int32))
+
+
+@pytest.mark.parametrize("cfg_index", [3, 5])
+def test_prefill_full_size_sampled_rows(gu, oracle, cfg_index):
+    """The benchmark's prefill launch at the full shape; the oracle checks sampled
+    rows one by one (first and last rows, page and block boundaries, seeded
+    picks) through its decode form on the truncated cache."""
+    cfg = wl.config(cfg_index)
+    lens = wl.prompt_lengths(cfg)
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    _say(f"prefill full cfg{cfg_index}: B={cfg.batch} rows={int(cu[-1])}")
+    _, ks, vs = wl.qkv(cfg, lens, device=gu.DEV)
+    q = wl.query_rows(cfg, int(cu[-1]), device=gu.DEV)
+    A = gu.FilledArena(cfg, lens, ks, vs)
+    try:
+        table, _, _ = A.host_state()
+        out = _run(gu, cfg, A, q, cu, int(lens.max()), out_dtype=rb.RLHF_F32)
+        assert torch.isfinite(out).all()
+        rng = np.random.default_rng(cfg.seed)
+        seqs = sorted({int(lens.argmin()), int(lens.argmax()), int(rng.integers(0, cfg.batch))})
+        worst = 0.0
+        for b in seqs:
+            L = int(lens[b])
+            picks = sorted({0, 1, 15, 16, 31, 32, 255, 256, L - 1, L - 2, *rng.integers(0, L, 6).tolist()} & set(range(L)))
+            kp, vp = wl.plain_pages([wl.to_storage(ks[b])], [wl.to_storage(vs[b])], table[b][None], A.n_pages)
+            for p in picks:
+                expect = oracle.decode_attention(wl.to_storage(q[cu[b] + p][None]), kp, vp, table[b][None],
+                                                 np.array([p + 1], dtype=np.int32), wl.DTYPE_CODE[cfg.kv_dtype])
+                got = out[cu[b] + p].cpu().numpy().astype(np.float64)
+                worst = max(worst, np.abs(got - expect[0]).max())
+        _say(f"  seqs {seqs}: max-abs err {worst:.3e}")
+        assert worst <= ATTN_TOL
+        # holds at any size: every output lies inside the range of its head's values
+        b = seqs[0]
+        G = cfg.n_q_heads // cfg.n_kv_heads
+        vmin, vmax = vs[b].float().amin(0), vs[b].float().amax(0)
+        o = out[cu[b]:cu[b + 1]].view(-1, cfg.n_kv_heads, G, cfg.head_dim)
+        assert (o >= vmin[None, :, None, :] - 1e-5).all() and (o <= vmax[None, :, None, :] + 1e-5).all()
+    finally:
+        A.close()
