@@ -6,32 +6,41 @@
 // meets hundreds of query rows -- so both products run on the matrix cores and
 // the kernel is bound by them, not by HBM.
 //
-// Work split.  A workgroup owns one (sequence, KV head) and a block of
-// consecutive new positions; its query rows are the pairs (position, head of
-// the KV head's group), flattened position-major.  Each of the four wavefronts
-// takes NT tiles of 16 such rows and walks the keys 0 .. (its last position) in
-// steps of 32 keys = two pages.  Workgroups are numbered so that those of one
-// (sequence, KV head) land on the same XCD one after the other (its K/V stays
-// in that XCD's L2) and the long, late position blocks start first.
+// Work split.  A workgroup (8 wavefronts, two per SIMD) owns one (sequence, KV
+// head) and a block of consecutive new positions; its 256 query rows are the
+// pairs (position, head of the KV head's group), flattened position-major.
+// Each wavefront keeps two tiles of 16 rows (q and the output accumulators) in
+// registers.  The workgroup walks the keys 0 .. (its last position) in steps of
+// 32 keys = two pages; the step's K and V blocks are copied once from the arena
+// into LDS (double-buffered, the next step's global loads in flight during the
+// current step) and every wavefront takes its matrix operands from there.
+// Workgroups are numbered so that those of one (sequence, KV head) land on the
+// same XCD one after the other (its K/V stays in that XCD's L2) and the long,
+// late position blocks start first.
 //
 // Per step and tile, with lane l = (g = l/16, c = l%16):
-//   S^T[key][row]   = K page (A operand, straight from the arena's block
-//                     layout) x q rows (B operand, held in registers): lane
-//                     (g, c) receives keys 4g..4g+3 of each page for row c;
+//   S^T[key][row]   = K page (A operand: the arena's K block layout is the
+//                     operand layout, lane l reads 16 bytes at granule 64k+l)
+//                     x q rows (B operand, registers): lane (g, c) receives
+//                     keys 4g..4g+3 of each page for row c;
 //   softmax         against a per-row reference exponent that is only moved
 //                     (and the accumulators rescaled) when some score exceeds
-//                     it by more than 2^kLift -- after the first few steps of
-//                     a row that never happens, so the common step has no
-//                     cross-lane traffic and no rescaling;
-//   O^T[dim][row]  += V^T (A operand: the lane's 4-slot granules of the two
-//                     pages side by side form the 8 contraction entries)
-//                     x P^T (B operand: exactly the registers S^T arrived in).
+//                     it by more than 2^kLift -- after the first steps of a row
+//                     that never happens, so the common step has no cross-lane
+//                     traffic and no rescaling;
+//   O^T[dim][row]  += V^T (A operand: in LDS the 4-key granules of the two
+//                     pages sit side by side, 16 bytes = the lane's 8
+//                     contraction entries) x P^T (B operand: exactly the
+//                     registers S^T arrived in).
 // Probabilities go in as a high and a low 16-bit part, so the result keeps
-// fp32-level accuracy.  Row sums stay per lane until the end.
+// fp32-level accuracy.  Row sums stay per lane until the end.  Steps that lie
+// entirely below a wavefront's first position need no mask; only the last few
+// ("edge") steps compare key and query positions and blank never-written keys.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
 #include <cmath>
+#include <type_traits>
 
 #include "common.h"
 #include "device_ops.h"
@@ -41,26 +50,51 @@ namespace rlhf {
 namespace {
 
 constexpr int kPage = RLHF_PAGE_TOKENS;
-constexpr int kThreads = 256;
-constexpr int kWgWaves = 4;
-constexpr int kTiles = 4;                          // 16-row tiles per wavefront
+constexpr int kThreads = 512;
+constexpr int kWgWaves = kThreads / 64;
+constexpr int kTiles = 2;                          // 16-row tiles per wavefront
 constexpr int kRowsPerWg = kWgWaves * kTiles * 16; // (position, head) rows per workgroup
+constexpr int kStepKeys = 2 * kPage;
 constexpr int kXcds = 8;
 constexpr float kLift = 8.0f;  // log2 units a score may exceed the reference before it is moved
 
-__device__ __forceinline__ uint4 load_cached(const uint16_t *p)
+// Packs the upper 16 bits of two words: `first` into the low half.
+__device__ __forceinline__ uint32_t pack_upper(uint32_t first, uint32_t second)
 {
-    return *reinterpret_cast<const uint4 *>(p);
+    return __builtin_amdgcn_perm(second, first, 0x07060302u);
 }
 
-template <int DT, int ODT, int D, int NT>
+// fp32 pair -> packed high parts and packed remainders (see split_pair); the
+// bf16 form truncates, which the remainder absorbs.
+template <int DT>
+__device__ __forceinline__ void split2(float p0, float p1, uint32_t &hi, uint32_t &lo)
+{
+    if constexpr (DT == RLHF_BF16) {
+        const uint32_t u0 = __float_as_uint(p0), u1 = __float_as_uint(p1);
+        hi = pack_upper(u0, u1);
+        const float r0 = p0 - __uint_as_float(u0 & 0xffff0000u);  // exact
+        const float r1 = p1 - __uint_as_float(u1 & 0xffff0000u);
+        lo = pack_upper(__float_as_uint(r0), __float_as_uint(r1));
+    } else {
+        split_pair<DT>(p0, p1, hi, lo);
+    }
+}
+
+template <int DT, int ODT, int D>
 __global__ __launch_bounds__(kThreads) void prefill_attn_kernel(
     const uint16_t *__restrict__ q, const int32_t *__restrict__ cu_q, const uint16_t *__restrict__ k_arena,
     const uint16_t *__restrict__ v_arena, const int32_t *__restrict__ page_table,
     const int32_t *__restrict__ seq_lens, void *__restrict__ out, int batch, int n_q_heads, int n_kv_heads,
     int mpps, int max_len, int n_blocks, int pos_per_wg, float scale_log2)
 {
-    constexpr int NL = D / 32;
+    constexpr int NT = kTiles;
+    constexpr int NL = D / 32;                 // contraction chunks of q.K
+    constexpr int ND = D / 16;                 // 16-dim output tiles
+    constexpr int kBlockBytes = kPage * D * 2; // one K (or V) block of a page and head
+    constexpr int kStageBytes = 4 * kBlockBytes;
+    constexpr int kItems = kBlockBytes / 8;    // 16-byte K items of two pages = V granule pairs
+    __shared__ __attribute__((aligned(16))) unsigned char stage[2][kStageBytes];
+
     // workgroup -> (unit, position block): units round-robin over the XCDs, the
     // blocks of a unit consecutive on its XCD, last block first
     const int xcd = blockIdx.x % kXcds, seq_no = blockIdx.x / kXcds;
@@ -74,25 +108,27 @@ __global__ __launch_bounds__(kThreads) void prefill_attn_kernel(
     const int L = min(seq_lens[b], max_len);
     const int i0 = pb * pos_per_wg;
     if (i0 >= n_b || n_b > L)
-        return;
+        return;                 // whole workgroup: no barrier has been reached
     const int first = L - n_b;  // position of the sequence's first query row
     const int rows_wg = pos_per_wg * group;
-
-    const int lane = threadIdx.x & 63, g = lane >> 4, c = lane & 15;
-    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int r_first = wv * NT * 16;
-    if (r_first >= rows_wg || i0 + r_first / group >= n_b)
-        return;  // nothing for this wavefront (no barriers below)
-    const int r_last = min(r_first + NT * 16, rows_wg) - 1;
-    const int p_min = first + i0 + r_first / group;
-    const int p_max = first + min(n_b - 1, i0 + r_last / group);
-    const int n_steps = p_max / 32 + 1;
+    const int n_steps = (first + min(n_b, i0 + pos_per_wg) - 1) / kStepKeys + 1;  // workgroup-wide
     const int n_pages = (L + kPage - 1) / kPage;
 
-    // this lane's row of each tile
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, g = lane >> 4, c = lane & 15;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // this wavefront's rows; one without rows still copies and synchronises
+    const int r_first = wv * NT * 16;
+    const bool active = r_first < rows_wg && i0 + r_first / group < n_b;
+    const int r_last = min(r_first + NT * 16, rows_wg) - 1;
+    const int p_min = first + i0 + r_first / group;
+    const int p_max = active ? first + min(n_b - 1, i0 + r_last / group) : -1;
+    const int n_plain = active ? (p_min + 1) / kStepKeys : 0;  // steps with every key visible to every row
+    const int s_last = p_max >= 0 ? p_max / kStepKeys : -1;    // last step with a visible key
+
     int pos[NT];
     bool valid[NT];
-    int64_t row_off[NT];  // element offset of the row in q / out
+    int64_t row_off[NT];  // element offset of the lane's row in q / out
     uint4 qr[NT][NL];
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
@@ -105,159 +141,184 @@ __global__ __launch_bounds__(kThreads) void prefill_attn_kernel(
         row_off[t] = ((int64_t)(q0 + i) * n_q_heads + hkv * group + hg) * D;
 #pragma unroll
         for (int k = 0; k < NL; ++k)
-            qr[t][k] = load_cached(q + row_off[t] + (4 * k + g) * 8);
+            qr[t][k] = *reinterpret_cast<const uint4 *>(q + row_off[t] + (4 * k + g) * 8);
     }
 
+    // ---- arena -> LDS copy of one step: thread i < kItems moves 16 bytes of K
+    // (page a for the first half of the items, page b for the second) and the
+    // V granule i of both pages (8 bytes each), stored side by side
     const int64_t page_stride = (int64_t)n_kv_heads * (kPage * D);
     const int64_t head_off = (int64_t)hkv * (kPage * D);
-    const int k_lane = lane * 8;             // K: granule 64*k + lane
-    const int v_lane = (g * D + 2 * c) * 4;  // V: granules (quad g, dims 32*k + 2c, +1)
     const int32_t *table = page_table + (int64_t)b * mpps;
-    auto load_step = [&](int s, uint4(&ka)[NL], uint4(&kb)[NL], uint4(&va)[NL], uint4(&vb)[NL]) {
+    const bool copier = tid < kItems;
+    const int k_sel = tid >= kItems / 2;
+    const int k_off = (tid - k_sel * (kItems / 2)) * 8;  // elements inside the K block
+    uint4 st_k;
+    uint2 st_va, st_vb;
+    auto fetch = [&](int s) {
         // the second page of the last step may not exist: re-read the last real
         // page instead; its keys lie beyond every position and are masked
         const int pa = table[min(2 * s, n_pages - 1)], pbb = table[min(2 * s + 1, n_pages - 1)];
         const int64_t base_a = (int64_t)pa * page_stride + head_off;
         const int64_t base_b = (int64_t)pbb * page_stride + head_off;
-#pragma unroll
-        for (int k = 0; k < NL; ++k) {
-            ka[k] = load_cached(k_arena + base_a + k_lane + k * 512);
-            kb[k] = load_cached(k_arena + base_b + k_lane + k * 512);
-            va[k] = load_cached(v_arena + base_a + v_lane + k * 128);
-            vb[k] = load_cached(v_arena + base_b + v_lane + k * 128);
+        if (copier) {
+            st_k = *reinterpret_cast<const uint4 *>(k_arena + (k_sel ? base_b : base_a) + k_off);
+            st_va = *reinterpret_cast<const uint2 *>(v_arena + base_a + tid * 4);
+            st_vb = *reinterpret_cast<const uint2 *>(v_arena + base_b + tid * 4);
+        }
+    };
+    auto deposit = [&](int buf) {
+        if (copier) {
+            *reinterpret_cast<uint4 *>(&stage[buf][tid * 16]) = st_k;
+            *reinterpret_cast<uint4 *>(&stage[buf][2 * kBlockBytes + tid * 16]) =
+                make_uint4(st_va.x, st_va.y, st_vb.x, st_vb.y);
         }
     };
 
     float m_ref[NT], l_part[NT];
-    f32x4_t o[NT][NL][2];
+    f32x4_t o[NT][ND];
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
         m_ref[t] = -INFINITY;
         l_part[t] = 0.f;
 #pragma unroll
-        for (int k = 0; k < NL; ++k)
-            o[t][k][0] = o[t][k][1] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        for (int k = 0; k < ND; ++k)
+            o[t][k] = f32x4_t{0.f, 0.f, 0.f, 0.f};
     }
 
-    auto process_step = [&](int s, const uint4(&ka)[NL], const uint4(&kb)[NL], const uint4(&va)[NL],
-                            const uint4(&vb)[NL]) {
-        const int key0 = 32 * s;
-        // Keys at or beyond L were never written (or belong to the stand-in page):
-        // their probability is 0 but their bits may be NaN, so blank V there.
-        uint32_t a01 = ~0u, a23 = ~0u, b01 = ~0u, b23 = ~0u;
-        if (key0 + 32 > L) {
-            const int ja = key0 + 4 * g, jb = ja + 16;
-            a01 = (ja + 0 < L ? 0x0000ffffu : 0u) | (ja + 1 < L ? 0xffff0000u : 0u);
-            a23 = (ja + 2 < L ? 0x0000ffffu : 0u) | (ja + 3 < L ? 0xffff0000u : 0u);
-            b01 = (jb + 0 < L ? 0x0000ffffu : 0u) | (jb + 1 < L ? 0xffff0000u : 0u);
-            b23 = (jb + 2 < L ? 0x0000ffffu : 0u) | (jb + 3 < L ? 0xffff0000u : 0u);
-        }
-        // V^T operands: the lane's 4-key granules of page a and page b side by side
-        uint4 v0[NL], v1[NL];
-#pragma unroll
-        for (int k = 0; k < NL; ++k) {
-            v0[k] = make_uint4(va[k].x & a01, va[k].y & a23, vb[k].x & b01, vb[k].y & b23);  // dim 32k + 2c
-            v1[k] = make_uint4(va[k].z & a01, va[k].w & a23, vb[k].z & b01, vb[k].w & b23);  // dim 32k + 2c + 1
-        }
-        const bool diagonal = key0 + 31 > p_min;  // some key of the step is hidden from some row
-#pragma unroll
-        for (int t = 0; t < NT; ++t) {
-            // S^T: keys 4g+j of page a (sa) and of page b (sb) for row c
-            f32x4_t sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
+    // One step of one wavefront.  kEdge: the step reaches past some row's
+    // position (mask by position) or past L (blank V of never-written keys).
+    auto process_step = [&](int s, int buf, auto edge) {
+        constexpr bool kEdge = decltype(edge)::value;
+        const int key0 = kStepKeys * s;
+        const unsigned char *sk = &stage[buf][0];
+        const unsigned char *sv = &stage[buf][2 * kBlockBytes];
+        // phase 1: scores and probabilities of both tiles (K operands live)
+        uint4 ph[NT], pl[NT];
+        {
+            uint4 ka[NL], kb[NL];
 #pragma unroll
             for (int k = 0; k < NL; ++k) {
-                sa = mfma_k32<DT>(ka[k], qr[t][k], sa);
-                sb = mfma_k32<DT>(kb[k], qr[t][k], sb);
+                ka[k] = *reinterpret_cast<const uint4 *>(sk + (k * 64 + lane) * 16);
+                kb[k] = *reinterpret_cast<const uint4 *>(sk + kBlockBytes + (k * 64 + lane) * 16);
             }
-            float y[8];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                y[j] = sa[j] * scale_log2;
-                y[4 + j] = sb[j] * scale_log2;
-            }
-            if (diagonal) {
-                const int lim = pos[t] - key0 - 4 * g;  // key offset j is visible iff j <= lim
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    y[j] = j <= lim ? y[j] : -INFINITY;
-                    y[4 + j] = 16 + j <= lim ? y[4 + j] : -INFINITY;
-                }
-            }
-            const float top = fmaxf(fmaxf(fmaxf(y[0], y[1]), fmaxf(y[2], y[3])),
-                                    fmaxf(fmaxf(y[4], y[5]), fmaxf(y[6], y[7])));
-            if (__any(top > m_ref[t] + kLift)) {
-                // move the reference of every row of the tile to its running maximum
-                float cm = fmaxf(top, __shfl_xor(top, 16));
-                cm = fmaxf(cm, __shfl_xor(cm, 32));
-                const float m_new = fmaxf(m_ref[t], cm);
-                const float alpha = fast_exp2(m_ref[t] - m_new);
-                m_ref[t] = m_new;
-                l_part[t] *= alpha;
+            for (int t = 0; t < NT; ++t) {
+                // S^T: keys 4g+j of page a (sa) and of page b (sb) for row c
+                f32x4_t sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int k = 0; k < NL; ++k) {
-                    o[t][k][0] *= alpha;
-                    o[t][k][1] *= alpha;
+                    sa = mfma_k32<DT>(ka[k], qr[t][k], sa);
+                    sb = mfma_k32<DT>(kb[k], qr[t][k], sb);
                 }
-            }
-            float p[8];
+                float x[8];
 #pragma unroll
-            for (int j = 0; j < 8; ++j)
-                p[j] = fast_exp2(y[j] - m_ref[t]);
-            l_part[t] += ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
-            uint4 ph, pl;
-            split_pair<DT>(p[0], p[1], ph.x, pl.x);
-            split_pair<DT>(p[2], p[3], ph.y, pl.y);
-            split_pair<DT>(p[4], p[5], ph.z, pl.z);
-            split_pair<DT>(p[6], p[7], ph.w, pl.w);
-            // O^T[dim][row] += V^T[dim][key] * P^T[key][row], 32 keys per product
+                for (int j = 0; j < 4; ++j) {
+                    x[j] = sa[j];
+                    x[4 + j] = sb[j];
+                }
+                if constexpr (kEdge) {
+                    const int lim = pos[t] - key0 - 4 * g;  // key offset j is visible iff j <= lim
 #pragma unroll
-            for (int k = 0; k < NL; ++k) {
-                o[t][k][0] = mfma_k32<DT>(v0[k], ph, o[t][k][0]);
-                o[t][k][0] = mfma_k32<DT>(v0[k], pl, o[t][k][0]);
-                o[t][k][1] = mfma_k32<DT>(v1[k], ph, o[t][k][1]);
-                o[t][k][1] = mfma_k32<DT>(v1[k], pl, o[t][k][1]);
+                    for (int j = 0; j < 4; ++j) {
+                        x[j] = j <= lim ? x[j] : -INFINITY;
+                        x[4 + j] = kPage + j <= lim ? x[4 + j] : -INFINITY;
+                    }
+                }
+                // scale_log2 > 0: the largest raw score is the largest scaled one
+                const float top = scale_log2 * fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])),
+                                                     fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+                if (__any(top > m_ref[t] + kLift)) {
+                    // move the reference of every row of the tile to its running maximum
+                    float cm = fmaxf(top, __shfl_xor(top, 16));
+                    cm = fmaxf(cm, __shfl_xor(cm, 32));
+                    const float m_new = fmaxf(m_ref[t], cm);
+                    const float alpha = fast_exp2(m_ref[t] - m_new);
+                    m_ref[t] = m_new;
+                    l_part[t] *= alpha;
+#pragma unroll
+                    for (int k = 0; k < ND; ++k)
+                        o[t][k] *= alpha;
+                }
+                float p[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    p[j] = fast_exp2(fmaf(x[j], scale_log2, -m_ref[t]));
+                l_part[t] += ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
+                split2<DT>(p[0], p[1], ph[t].x, pl[t].x);
+                split2<DT>(p[2], p[3], ph[t].y, pl[t].y);
+                split2<DT>(p[4], p[5], ph[t].z, pl[t].z);
+                split2<DT>(p[6], p[7], ph[t].w, pl[t].w);
             }
+        }
+        // phase 2: O^T[dim][row] += V^T[dim][key] * P^T[key][row], 32 keys per product.
+        // V^T operand k: rows = dims 16k + c, entries = keys 4g..4g+3 of page a, then of page b
+        uint32_t a01 = ~0u, a23 = ~0u, b01 = ~0u, b23 = ~0u;
+        if constexpr (kEdge) {
+            if (key0 + kStepKeys > L) {  // blank never-written keys: 0 * NaN must not reach the product
+                const int ja = key0 + 4 * g, jb = ja + kPage;
+                a01 = (ja + 0 < L ? 0x0000ffffu : 0u) | (ja + 1 < L ? 0xffff0000u : 0u);
+                a23 = (ja + 2 < L ? 0x0000ffffu : 0u) | (ja + 3 < L ? 0xffff0000u : 0u);
+                b01 = (jb + 0 < L ? 0x0000ffffu : 0u) | (jb + 1 < L ? 0xffff0000u : 0u);
+                b23 = (jb + 2 < L ? 0x0000ffffu : 0u) | (jb + 3 < L ? 0xffff0000u : 0u);
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < ND; ++k) {
+            uint4 vop = *reinterpret_cast<const uint4 *>(sv + (g * D + 16 * k + c) * 16);
+            if constexpr (kEdge)
+                vop = make_uint4(vop.x & a01, vop.y & a23, vop.z & b01, vop.w & b23);
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+                o[t][k] = mfma_k32<DT>(vop, ph[t], o[t][k]);
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+                o[t][k] = mfma_k32<DT>(vop, pl[t], o[t][k]);
         }
     };
+    auto step = [&](int s, int buf) {
+        if (s < n_plain)
+            process_step(s, buf, std::false_type{});
+        else if (s <= s_last)
+            process_step(s, buf, std::true_type{});
+    };
 
-    // one step ahead; the last step is peeled so that the prefetch in the loop is
-    // unconditional
-    uint4 ka[NL], kb[NL], va[NL], vb[NL];
-    load_step(0, ka, kb, va, vb);
+    // Pipeline: while step s is computed out of one LDS buffer, the global loads
+    // of step s+1 are in flight; they are written to the other buffer after the
+    // computation, and one barrier per step orders both the hand-over of that
+    // buffer and the reuse of the current one.  The last step is peeled so that
+    // the prefetch in the loop is unconditional.
+    fetch(0);
+    deposit(0);
+    __syncthreads();
     for (int s = 0; s + 1 < n_steps; ++s) {
-        uint4 kan[NL], kbn[NL], van[NL], vbn[NL];
-        load_step(s + 1, kan, kbn, van, vbn);
-        process_step(s, ka, kb, va, vb);
-#pragma unroll
-        for (int k = 0; k < NL; ++k) {
-            ka[k] = kan[k];
-            kb[k] = kbn[k];
-            va[k] = van[k];
-            vb[k] = vbn[k];
-        }
+        fetch(s + 1);
+        step(s, s & 1);
+        deposit((s + 1) & 1);
+        __syncthreads();
     }
-    process_step(n_steps - 1, ka, kb, va, vb);
+    step(n_steps - 1, (n_steps - 1) & 1);
 
-    // o[t][k][e][j] is dim 32k + 2(4g+j) + e of row c
+    // o[t][k][j] is dim 16k + 4g + j of row c
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
         float l_all = l_part[t] + __shfl_xor(l_part[t], 16);
         l_all += __shfl_xor(l_all, 32);
-        if (!valid[t])
+        if (!active || !valid[t])
             continue;
         const float inv = 1.0f / l_all;
 #pragma unroll
-        for (int k = 0; k < NL; ++k)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const float x0 = o[t][k][0][j] * inv, x1 = o[t][k][1][j] * inv;
-                const int64_t idx = row_off[t] + 32 * k + 2 * (4 * g + j);
-                if constexpr (ODT == RLHF_F32)
-                    *(float2 *)((float *)out + idx) = make_float2(x0, x1);
-                else
-                    *(uint32_t *)((uint16_t *)out + idx) =
-                        (uint32_t)pack16<ODT>(x0) | ((uint32_t)pack16<ODT>(x1) << 16);
-            }
+        for (int k = 0; k < ND; ++k) {
+            const int64_t idx = row_off[t] + 16 * k + 4 * g;
+            const float x0 = o[t][k][0] * inv, x1 = o[t][k][1] * inv, x2 = o[t][k][2] * inv,
+                        x3 = o[t][k][3] * inv;
+            if constexpr (ODT == RLHF_F32)
+                *(float4 *)((float *)out + idx) = make_float4(x0, x1, x2, x3);
+            else
+                *(uint2 *)((uint16_t *)out + idx) =
+                    make_uint2((uint32_t)pack16<ODT>(x0) | ((uint32_t)pack16<ODT>(x1) << 16),
+                               (uint32_t)pack16<ODT>(x2) | ((uint32_t)pack16<ODT>(x3) << 16));
+        }
     }
 }
 
@@ -275,7 +336,7 @@ int launch(const rlhf_attn_params &p, const void *q, const int32_t *cu_q, int ma
         return fail(RLHF_ERR_UNSUPPORTED, "prefill launch of %lld workgroups: split the call", (long long)grid);
     const int cap = p.max_pages_per_seq * kPage;
     const int max_len = (p.max_seq_len > 0 && p.max_seq_len < cap) ? p.max_seq_len : cap;
-    hipLaunchKernelGGL((prefill_attn_kernel<DT, ODT, D, kTiles>), dim3((unsigned)grid), dim3(kThreads), 0, s,
+    hipLaunchKernelGGL((prefill_attn_kernel<DT, ODT, D>), dim3((unsigned)grid), dim3(kThreads), 0, s,
                        (const uint16_t *)q, cu_q, (const uint16_t *)k_arena, (const uint16_t *)v_arena,
                        page_table, seq_lens, out, p.batch, p.n_q_heads, p.n_kv_heads, p.max_pages_per_seq,
                        max_len, n_blocks, pos_per_wg, scale * kLog2e);
@@ -324,6 +385,8 @@ extern "C" int rlhf_prefill_attention(const rlhf_attn_params *params, const void
     if ((int64_t)p.max_pages_per_seq * kPage > 0x7fffffffLL ||
         (int64_t)p.batch * p.max_pages_per_seq > 0x7fffffffLL)
         return fail(RLHF_ERR_INVALID, "page table too large");
+    if (p.softmax_scale < 0.f)
+        return fail(RLHF_ERR_INVALID, "softmax_scale must not be negative");
     if (p.batch == 0 || max_q_len == 0)
         return RLHF_OK;
     if (!q || !cu_q || !k_arena || !v_arena || !page_table || !seq_lens || !out)

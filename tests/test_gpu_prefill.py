@@ -113,9 +113,12 @@ def test_prefill_first_row_is_its_value_row_and_skipped_sequences_stay_untouched
     try:
         out = _run(gu, cfg, A, q, cu, 40, out_dtype=rb.RLHF_F32)
         assert torch.isnan(out[cu[1]:cu[2]]).all()                       # skipped, as documented
-        for h in range(4):                                              # position 0 sees one key: exactly V_0
-            assert torch.equal(out[0, h], vs[0][0, h // 2].float())
-            assert torch.equal(out[cu[2], h], vs[2][0, h // 2].float())
+        out16 = _run(gu, cfg, A, q, cu, 40)
+        for h in range(4):                        # position 0 sees one key: V_0 (to the rounding of the weights)
+            for row, b in ((0, 0), (int(cu[2]), 2)):
+                v0 = vs[b][0, h // 2]
+                assert (out[row, h] - v0.float()).abs().max().item() <= 1e-4
+                assert torch.equal(out16[row, h].view(torch.int16), v0.view(torch.int16))
         keep = [0, 2, 3]
         table, _, _ = A.host_state()
         cu_k = np.concatenate([[0], np.cumsum(n_new[keep])]).astype(np.int32)
