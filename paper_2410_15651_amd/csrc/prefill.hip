@@ -64,6 +64,14 @@ __device__ __forceinline__ uint32_t pack_upper(uint32_t first, uint32_t second)
     return __builtin_amdgcn_perm(second, first, 0x07060302u);
 }
 
+// max(a, b) as median(a, b, +inf): one instruction, and no NaN-quieting move in
+// front of it as the generic fmaxf needs for a matrix-core result (scores are
+// finite or -inf here).
+__device__ __forceinline__ float max2(float a, float b)
+{
+    return __builtin_amdgcn_fmed3f(a, b, INFINITY);
+}
+
 // fp32 pair -> packed high parts and packed remainders (see split_pair); the
 // bf16 form truncates, which the remainder absorbs.
 template <int DT>
@@ -226,8 +234,8 @@ __global__ __launch_bounds__(kThreads) void prefill_attn_kernel(
                     }
                 }
                 // scale_log2 > 0: the largest raw score is the largest scaled one
-                const float top = scale_log2 * fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])),
-                                                     fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+                const float top = scale_log2 * max2(max2(max2(x[0], x[1]), max2(x[2], x[3])),
+                                                    max2(max2(x[4], x[5]), max2(x[6], x[7])));
                 if (__any(top > m_ref[t] + kLift)) {
                     // move the reference of every row of the tile to its running maximum
                     float cm = fmaxf(top, __shfl_xor(top, 16));
@@ -276,28 +284,37 @@ __global__ __launch_bounds__(kThreads) void prefill_attn_kernel(
                 o[t][k] = mfma_k32<DT>(vop, pl[t], o[t][k]);
         }
     };
-    auto step = [&](int s, int buf) {
-        if (s < n_plain)
-            process_step(s, buf, std::false_type{});
-        else if (s <= s_last)
-            process_step(s, buf, std::true_type{});
-    };
-
     // Pipeline: while step s is computed out of one LDS buffer, the global loads
     // of step s+1 are in flight; they are written to the other buffer after the
     // computation, and one barrier per step orders both the hand-over of that
-    // buffer and the reuse of the current one.  The last step is peeled so that
-    // the prefetch in the loop is unconditional.
+    // buffer and the reuse of the current one.  Every wavefront passes the same
+    // n_steps - 1 barriers, but spends them in two loops of its own lengths: its
+    // mask-free steps first, then its edge steps (and steps past its last
+    // position, where it only copies).  The last step is peeled so that the
+    // prefetch in the loops is unconditional.
     fetch(0);
     deposit(0);
+    // Everything loaded so far (q included) has arrived before the loops start:
+    // otherwise the wait counters inside them must allow for q still being in
+    // flight, which in steady state means waiting for the prefetch just issued.
+    __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
-    for (int s = 0; s + 1 < n_steps; ++s) {
+    int s = 0;
+    for (const int s_end = min(n_plain, n_steps - 1); s < s_end; ++s) {
         fetch(s + 1);
-        step(s, s & 1);
+        process_step(s, s & 1, std::false_type{});
         deposit((s + 1) & 1);
         __syncthreads();
     }
-    step(n_steps - 1, (n_steps - 1) & 1);
+    for (; s + 1 < n_steps; ++s) {
+        fetch(s + 1);
+        if (s <= s_last)
+            process_step(s, s & 1, std::true_type{});
+        deposit((s + 1) & 1);
+        __syncthreads();
+    }
+    if (s <= s_last)
+        process_step(s, s & 1, std::true_type{});
 
     // o[t][k][j] is dim 16k + 4g + j of row c
 #pragma unroll
