@@ -16,6 +16,7 @@ typedef __attribute__((ext_vector_type(8))) _Float16 f16x8_t;
 typedef __attribute__((ext_vector_type(4))) short s16x4_t;
 typedef __attribute__((ext_vector_type(4))) _Float16 f16x4_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 
 // D[16x16] += A[16x32] * B[32x16]; lane l supplies row (A) / column (B) l%16 and
 // the 8 contraction entries of group l/16; it receives D[4*(l/16)+j][l%16].
@@ -27,6 +28,21 @@ __device__ __forceinline__ f32x4_t mfma_k32(const uint4 &a, const uint4 &b, f32x
                                                        __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
     else
         return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, a),
+                                                      __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
+}
+
+// D[32x32] += A[32x16] * B[16x32]; lane l supplies row (A) / column (B) l%32 and
+// the 8 contraction entries of half l/32; it receives, in register r, the
+// element D[8*(r/4) + 4*(l/32) + r%4][l%32].  One wavefront issues these at the
+// matrix cores' full rate, which the 16x16 shapes do not reach.
+template <int DT>
+__device__ __forceinline__ f32x16_t mfma_32x32(const uint4 &a, const uint4 &b, f32x16_t c)
+{
+    if constexpr (DT == RLHF_BF16)
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a),
+                                                       __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, a),
                                                       __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
 }
 

@@ -9,7 +9,7 @@
 // Work split.  A workgroup (8 wavefronts, two per SIMD) owns one (sequence, KV
 // head) and a block of consecutive new positions; its 256 query rows are the
 // pairs (position, head of the KV head's group), flattened position-major.
-// Each wavefront keeps two tiles of 16 rows (q and the output accumulators) in
+// Each wavefront keeps one tile of 32 rows (q and the output accumulators) in
 // registers.  The workgroup walks the keys 0 .. (its last position) in steps of
 // 32 keys = two pages; the step's K and V blocks are copied once from the arena
 // into LDS (double-buffered, the next step's global loads in flight during the
@@ -18,20 +18,22 @@
 // same XCD one after the other (its K/V stays in that XCD's L2) and the long,
 // late position blocks start first.
 //
-// Per step and tile, with lane l = (g = l/16, c = l%16):
-//   S^T[key][row]   = K page (A operand: the arena's K block layout is the
-//                     operand layout, lane l reads 16 bytes at granule 64k+l)
-//                     x q rows (B operand, registers): lane (g, c) receives
-//                     keys 4g..4g+3 of each page for row c;
+// All products are 32x32x16 matrix-core instructions (the shape one wavefront
+// can issue at full rate).  Per step, with lane l = (h = l/32, c = l%32):
+//   S^T[key][row]   = K (A operand: in LDS the two pages' K granules are
+//                     interleaved to [dim/8][32 keys][8 dims], so lane l reads
+//                     16 contiguous bytes at granule 64*i + l) x q rows (B
+//                     operand, registers): lane (h, c) receives, for row c, the
+//                     16 keys 8*(r/4) + 4h + r%4, r = 0..15;
 //   softmax         against a per-row reference exponent that is only moved
 //                     (and the accumulators rescaled) when some score exceeds
 //                     it by more than 2^kLift -- after the first steps of a row
 //                     that never happens, so the common step has no cross-lane
 //                     traffic and no rescaling;
-//   O^T[dim][row]  += V^T (A operand: in LDS the 4-key granules of the two
-//                     pages sit side by side, 16 bytes = the lane's 8
-//                     contraction entries) x P^T (B operand: exactly the
-//                     registers S^T arrived in).
+//   O^T[dim][row]  += V^T (A operand: in LDS the 4-key granules are paired so
+//                     that 16 bytes hold exactly the 8 keys the lane's half h
+//                     contributes) x P^T (B operand: the registers S^T arrived
+//                     in, first 8 for the first page, last 8 for the second).
 // Probabilities go in as a high and a low 16-bit part, so the result keeps
 // fp32-level accuracy.  Row sums stay per lane until the end.  Steps that lie
 // entirely below a wavefront's first position need no mask; only the last few
@@ -52,8 +54,8 @@ namespace {
 constexpr int kPage = RLHF_PAGE_TOKENS;
 constexpr int kThreads = 512;
 constexpr int kWgWaves = kThreads / 64;
-constexpr int kTiles = 2;                          // 16-row tiles per wavefront
-constexpr int kRowsPerWg = kWgWaves * kTiles * 16; // (position, head) rows per workgroup
+constexpr int kTileRows = 32;                      // query rows per wavefront
+constexpr int kRowsPerWg = kWgWaves * kTileRows;   // (position, head) rows per workgroup
 constexpr int kStepKeys = 2 * kPage;
 constexpr int kXcds = 8;
 constexpr float kLift = 8.0f;  // log2 units a score may exceed the reference before it is moved
@@ -62,14 +64,6 @@ constexpr float kLift = 8.0f;  // log2 units a score may exceed the reference be
 __device__ __forceinline__ uint32_t pack_upper(uint32_t first, uint32_t second)
 {
     return __builtin_amdgcn_perm(second, first, 0x07060302u);
-}
-
-// max(a, b) as median(a, b, +inf): one instruction, and no NaN-quieting move in
-// front of it as the generic fmaxf needs for a matrix-core result (scores are
-// finite or -inf here).
-__device__ __forceinline__ float max2(float a, float b)
-{
-    return __builtin_amdgcn_fmed3f(a, b, INFINITY);
 }
 
 // fp32 pair -> packed high parts and packed remainders (see split_pair); the
@@ -95,12 +89,12 @@ __global__ __launch_bounds__(kThreads) void prefill_attn_kernel(
     const int32_t *__restrict__ seq_lens, void *__restrict__ out, int batch, int n_q_heads, int n_kv_heads,
     int mpps, int max_len, int n_blocks, int pos_per_wg, float scale_log2)
 {
-    constexpr int NT = kTiles;
-    constexpr int NL = D / 32;                 // contraction chunks of q.K
-    constexpr int ND = D / 16;                 // 16-dim output tiles
+    constexpr int NC = D / 16;                 // 16-dim contraction chunks of q.K
+    constexpr int ND = D / 32;                 // 32-dim output tiles
     constexpr int kBlockBytes = kPage * D * 2; // one K (or V) block of a page and head
     constexpr int kStageBytes = 4 * kBlockBytes;
-    constexpr int kItems = kBlockBytes / 8;    // 16-byte K items of two pages = V granule pairs
+    constexpr int kItems = kBlockBytes / 8;    // 16-byte copy items of K (two pages) = of V
+    constexpr int kCopies = (kItems + kThreads - 1) / kThreads;
     __shared__ __attribute__((aligned(16))) unsigned char stage[2][kStageBytes];
 
     // workgroup -> (unit, position block): units round-robin over the XCDs, the
@@ -123,76 +117,89 @@ __global__ __launch_bounds__(kThreads) void prefill_attn_kernel(
     const int n_pages = (L + kPage - 1) / kPage;
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63, g = lane >> 4, c = lane & 15;
+    const int lane = tid & 63, h = lane >> 5, c = lane & 31;
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
     // this wavefront's rows; one without rows still copies and synchronises
-    const int r_first = wv * NT * 16;
+    const int r_first = wv * kTileRows;
     const bool active = r_first < rows_wg && i0 + r_first / group < n_b;
-    const int r_last = min(r_first + NT * 16, rows_wg) - 1;
+    const int r_last = min(r_first + kTileRows, rows_wg) - 1;
     const int p_min = first + i0 + r_first / group;
     const int p_max = active ? first + min(n_b - 1, i0 + r_last / group) : -1;
     const int n_plain = active ? (p_min + 1) / kStepKeys : 0;  // steps with every key visible to every row
     const int s_last = p_max >= 0 ? p_max / kStepKeys : -1;    // last step with a visible key
 
-    int pos[NT];
-    bool valid[NT];
-    int64_t row_off[NT];  // element offset of the lane's row in q / out
-    uint4 qr[NT][NL];
+    // the lane's row: q as the B operand of chunk i = dims 16i + 8h .. +8
+    const int r_raw = r_first + c;
+    const int r = min(r_raw, rows_wg - 1);
+    const int il = r / group, hg = r - il * group;
+    const int i_row = min(i0 + il, n_b - 1);
+    const bool valid = active && r_raw < rows_wg && i0 + il < n_b;
+    const int pos = first + i_row;
+    const int64_t row_off = ((int64_t)(q0 + i_row) * n_q_heads + hkv * group + hg) * D;
+    uint4 qr[NC];
 #pragma unroll
-    for (int t = 0; t < NT; ++t) {
-        const int r_raw = r_first + t * 16 + c;
-        const int r = min(r_raw, rows_wg - 1);
-        const int il = r / group, hg = r - il * group;
-        const int i = min(i0 + il, n_b - 1);
-        valid[t] = r_raw < rows_wg && i0 + il < n_b;
-        pos[t] = first + i;
-        row_off[t] = ((int64_t)(q0 + i) * n_q_heads + hkv * group + hg) * D;
-#pragma unroll
-        for (int k = 0; k < NL; ++k)
-            qr[t][k] = *reinterpret_cast<const uint4 *>(q + row_off[t] + (4 * k + g) * 8);
-    }
+    for (int i = 0; i < NC; ++i)
+        qr[i] = *reinterpret_cast<const uint4 *>(q + row_off + 16 * i + 8 * h);
 
-    // ---- arena -> LDS copy of one step: thread i < kItems moves 16 bytes of K
-    // (page a for the first half of the items, page b for the second) and the
-    // V granule i of both pages (8 bytes each), stored side by side
+    // ---- arena -> LDS copy of one step, thread tid moving items tid, tid + kThreads, ...
+    // K item: 16 bytes = 8 dims of one key; arena granule (dim/8, slot) of page
+    //   a or b goes to granule (dim/8)*32 + 16*page + slot.
+    // V item (page, half hh, dim): the arena's 4-key granules of quads hh and
+    //   hh + 2 for that dim (8 bytes each) go side by side to granule
+    //   (2*page + hh)*D + dim: the 8 keys 4hh..4hh+3, 8+4hh..8+4hh+3 of the page.
     const int64_t page_stride = (int64_t)n_kv_heads * (kPage * D);
     const int64_t head_off = (int64_t)hkv * (kPage * D);
     const int32_t *table = page_table + (int64_t)b * mpps;
-    const bool copier = tid < kItems;
-    const int k_sel = tid >= kItems / 2;
-    const int k_off = (tid - k_sel * (kItems / 2)) * 8;  // elements inside the K block
-    uint4 st_k;
-    uint2 st_va, st_vb;
-    auto fetch = [&](int s) {
-        // the second page of the last step may not exist: re-read the last real
-        // page instead; its keys lie beyond every position and are masked
-        const int pa = table[min(2 * s, n_pages - 1)], pbb = table[min(2 * s + 1, n_pages - 1)];
+    struct Staged {  // one step's copy items in registers, between the global load and the LDS store
+        uint4 k[kCopies];
+        uint2 v0[kCopies], v1[kCopies];
+    };
+    // Page ids of a step.  Steps past the end, and the second page of a last
+    // step that has only one, stand in the sequence's last real page: its keys
+    // lie beyond every position and are masked (or the copy is never used).
+    auto page_ids = [&](int s, int &pa, int &pbb) {
+        pa = table[min(2 * s, n_pages - 1)];
+        pbb = table[min(2 * s + 1, n_pages - 1)];
+    };
+    auto fetch = [&](Staged &st, int pa, int pbb) {
         const int64_t base_a = (int64_t)pa * page_stride + head_off;
         const int64_t base_b = (int64_t)pbb * page_stride + head_off;
-        if (copier) {
-            st_k = *reinterpret_cast<const uint4 *>(k_arena + (k_sel ? base_b : base_a) + k_off);
-            st_va = *reinterpret_cast<const uint2 *>(v_arena + base_a + tid * 4);
-            st_vb = *reinterpret_cast<const uint2 *>(v_arena + base_b + tid * 4);
+#pragma unroll
+        for (int i = 0; i < kCopies; ++i) {
+            const int item = tid + i * kThreads;
+            if (kItems % kThreads == 0 || item < kItems) {
+                const bool second = item >= kItems / 2;  // page b
+                const int within = item - (second ? kItems / 2 : 0);
+                const int64_t base = second ? base_b : base_a;
+                st.k[i] = *reinterpret_cast<const uint4 *>(k_arena + base + within * 8);
+                const int hh = within / D, dim = within - hh * D;
+                st.v0[i] = *reinterpret_cast<const uint2 *>(v_arena + base + (hh * D + dim) * 4);
+                st.v1[i] = *reinterpret_cast<const uint2 *>(v_arena + base + ((hh + 2) * D + dim) * 4);
+            }
         }
     };
-    auto deposit = [&](int buf) {
-        if (copier) {
-            *reinterpret_cast<uint4 *>(&stage[buf][tid * 16]) = st_k;
-            *reinterpret_cast<uint4 *>(&stage[buf][2 * kBlockBytes + tid * 16]) =
-                make_uint4(st_va.x, st_va.y, st_vb.x, st_vb.y);
+    auto deposit = [&](const Staged &st, int buf) {
+#pragma unroll
+        for (int i = 0; i < kCopies; ++i) {
+            const int item = tid + i * kThreads;
+            if (kItems % kThreads == 0 || item < kItems) {
+                const int second = item >= kItems / 2;
+                const int within = item - second * (kItems / 2);
+                const int d8 = within >> 4, slot = within & 15;
+                *reinterpret_cast<uint4 *>(&stage[buf][(d8 * 32 + 16 * second + slot) * 16]) = st.k[i];
+                *reinterpret_cast<uint4 *>(&stage[buf][2 * kBlockBytes + item * 16]) =
+                    make_uint4(st.v0[i].x, st.v0[i].y, st.v1[i].x, st.v1[i].y);
+            }
         }
     };
 
-    float m_ref[NT], l_part[NT];
-    f32x4_t o[NT][ND];
+    float m_ref = -INFINITY, l_part = 0.f;
+    f32x16_t o[ND];
 #pragma unroll
-    for (int t = 0; t < NT; ++t) {
-        m_ref[t] = -INFINITY;
-        l_part[t] = 0.f;
+    for (int k = 0; k < ND; ++k)
 #pragma unroll
-        for (int k = 0; k < ND; ++k)
-            o[t][k] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-    }
+        for (int j = 0; j < 16; ++j)
+            o[k][j] = 0.f;
 
     // One step of one wavefront.  kEdge: the step reaches past some row's
     // position (mask by position) or past L (blank V of never-written keys).
@@ -201,141 +208,146 @@ __global__ __launch_bounds__(kThreads) void prefill_attn_kernel(
         const int key0 = kStepKeys * s;
         const unsigned char *sk = &stage[buf][0];
         const unsigned char *sv = &stage[buf][2 * kBlockBytes];
-        // phase 1: scores and probabilities of both tiles (K operands live)
-        uint4 ph[NT], pl[NT];
-        {
-            uint4 ka[NL], kb[NL];
+        // S^T: register r holds key 8*(r/4) + 4h + r%4 of the step for row c
+        f32x16_t sc;
 #pragma unroll
-            for (int k = 0; k < NL; ++k) {
-                ka[k] = *reinterpret_cast<const uint4 *>(sk + (k * 64 + lane) * 16);
-                kb[k] = *reinterpret_cast<const uint4 *>(sk + kBlockBytes + (k * 64 + lane) * 16);
-            }
+        for (int j = 0; j < 16; ++j)
+            sc[j] = 0.f;
 #pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                // S^T: keys 4g+j of page a (sa) and of page b (sb) for row c
-                f32x4_t sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int k = 0; k < NL; ++k) {
-                    sa = mfma_k32<DT>(ka[k], qr[t][k], sa);
-                    sb = mfma_k32<DT>(kb[k], qr[t][k], sb);
-                }
-                float x[8];
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    x[j] = sa[j];
-                    x[4 + j] = sb[j];
-                }
-                if constexpr (kEdge) {
-                    const int lim = pos[t] - key0 - 4 * g;  // key offset j is visible iff j <= lim
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        x[j] = j <= lim ? x[j] : -INFINITY;
-                        x[4 + j] = kPage + j <= lim ? x[4 + j] : -INFINITY;
-                    }
-                }
-                // scale_log2 > 0: the largest raw score is the largest scaled one
-                const float top = scale_log2 * max2(max2(max2(x[0], x[1]), max2(x[2], x[3])),
-                                                    max2(max2(x[4], x[5]), max2(x[6], x[7])));
-                if (__any(top > m_ref[t] + kLift)) {
-                    // move the reference of every row of the tile to its running maximum
-                    float cm = fmaxf(top, __shfl_xor(top, 16));
-                    cm = fmaxf(cm, __shfl_xor(cm, 32));
-                    const float m_new = fmaxf(m_ref[t], cm);
-                    const float alpha = fast_exp2(m_ref[t] - m_new);
-                    m_ref[t] = m_new;
-                    l_part[t] *= alpha;
-#pragma unroll
-                    for (int k = 0; k < ND; ++k)
-                        o[t][k] *= alpha;
-                }
-                float p[8];
-#pragma unroll
-                for (int j = 0; j < 8; ++j)
-                    p[j] = fast_exp2(fmaf(x[j], scale_log2, -m_ref[t]));
-                l_part[t] += ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
-                split2<DT>(p[0], p[1], ph[t].x, pl[t].x);
-                split2<DT>(p[2], p[3], ph[t].y, pl[t].y);
-                split2<DT>(p[4], p[5], ph[t].z, pl[t].z);
-                split2<DT>(p[6], p[7], ph[t].w, pl[t].w);
-            }
+        for (int i = 0; i < NC; ++i) {
+            const uint4 kop = *reinterpret_cast<const uint4 *>(sk + (64 * i + lane) * 16);
+            sc = mfma_32x32<DT>(kop, qr[i], sc);
         }
-        // phase 2: O^T[dim][row] += V^T[dim][key] * P^T[key][row], 32 keys per product.
-        // V^T operand k: rows = dims 16k + c, entries = keys 4g..4g+3 of page a, then of page b
-        uint32_t a01 = ~0u, a23 = ~0u, b01 = ~0u, b23 = ~0u;
+        float x[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j)
+            x[j] = sc[j];
         if constexpr (kEdge) {
-            if (key0 + kStepKeys > L) {  // blank never-written keys: 0 * NaN must not reach the product
-                const int ja = key0 + 4 * g, jb = ja + kPage;
-                a01 = (ja + 0 < L ? 0x0000ffffu : 0u) | (ja + 1 < L ? 0xffff0000u : 0u);
-                a23 = (ja + 2 < L ? 0x0000ffffu : 0u) | (ja + 3 < L ? 0xffff0000u : 0u);
-                b01 = (jb + 0 < L ? 0x0000ffffu : 0u) | (jb + 1 < L ? 0xffff0000u : 0u);
-                b23 = (jb + 2 < L ? 0x0000ffffu : 0u) | (jb + 3 < L ? 0xffff0000u : 0u);
-            }
+            const int lim = pos - key0 - 4 * h;  // key offset 8*(r/4) + r%4 is visible iff <= lim
+#pragma unroll
+            for (int j = 0; j < 16; ++j)
+                x[j] = 8 * (j / 4) + j % 4 <= lim ? x[j] : -INFINITY;
         }
+        // Move the reference of the rows up to their running maximum when some
+        // score exceeds it by more than 2^kLift (rare after a row's first steps).
+        // scale_log2 > 0: the largest raw score is the largest scaled one.
+        float top = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+        top = fmaxf(top, fmaxf(fmaxf(fmaxf(x[8], x[9]), fmaxf(x[10], x[11])),
+                               fmaxf(fmaxf(x[12], x[13]), fmaxf(x[14], x[15]))));
+        top *= scale_log2;
+        if (__any(top > m_ref + kLift)) {
+            const float cm = fmaxf(top, __shfl_xor(top, 32));
+            const float m_new = fmaxf(m_ref, cm);
+            const float alpha = fast_exp2(m_ref - m_new);
+            m_ref = m_new;
+            l_part *= alpha;
 #pragma unroll
-        for (int k = 0; k < ND; ++k) {
-            uint4 vop = *reinterpret_cast<const uint4 *>(sv + (g * D + 16 * k + c) * 16);
-            if constexpr (kEdge)
-                vop = make_uint4(vop.x & a01, vop.y & a23, vop.z & b01, vop.w & b23);
+            for (int k = 0; k < ND; ++k)
+                o[k] *= alpha;
+        }
+        float p[16];
 #pragma unroll
-            for (int t = 0; t < NT; ++t)
-                o[t][k] = mfma_k32<DT>(vop, ph[t], o[t][k]);
+        for (int j = 0; j < 16; ++j)
+            p[j] = fast_exp2(fmaf(x[j], scale_log2, -m_ref));
+        l_part += (((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]))) +
+                  (((p[8] + p[9]) + (p[10] + p[11])) + ((p[12] + p[13]) + (p[14] + p[15])));
+        // P^T as B operands: entries 8h..8h+7 of page a are registers 0..7, of page b 8..15
+        uint4 ph[2], pl[2];
 #pragma unroll
-            for (int t = 0; t < NT; ++t)
-                o[t][k] = mfma_k32<DT>(vop, pl[t], o[t][k]);
+        for (int e = 0; e < 2; ++e) {
+            split2<DT>(p[8 * e + 0], p[8 * e + 1], ph[e].x, pl[e].x);
+            split2<DT>(p[8 * e + 2], p[8 * e + 3], ph[e].y, pl[e].y);
+            split2<DT>(p[8 * e + 4], p[8 * e + 5], ph[e].z, pl[e].z);
+            split2<DT>(p[8 * e + 6], p[8 * e + 7], ph[e].w, pl[e].w);
+        }
+        // O^T[dim][row] += V^T[dim][key] * P^T[key][row], 16 keys (one page) per product
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            uint32_t m01 = ~0u, m23 = ~0u, m45 = ~0u, m67 = ~0u;
+            if constexpr (kEdge) {
+                if (key0 + kStepKeys > L) {  // blank never-written keys: 0 * NaN must not reach the product
+                    const int j0 = key0 + kPage * e + 4 * h, j1 = j0 + 8;
+                    m01 = (j0 + 0 < L ? 0x0000ffffu : 0u) | (j0 + 1 < L ? 0xffff0000u : 0u);
+                    m23 = (j0 + 2 < L ? 0x0000ffffu : 0u) | (j0 + 3 < L ? 0xffff0000u : 0u);
+                    m45 = (j1 + 0 < L ? 0x0000ffffu : 0u) | (j1 + 1 < L ? 0xffff0000u : 0u);
+                    m67 = (j1 + 2 < L ? 0x0000ffffu : 0u) | (j1 + 3 < L ? 0xffff0000u : 0u);
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < ND; ++k) {
+                // rows = dims 32k + c, entries = keys 4h..4h+3 and 8+4h..8+4h+3 of page e
+                uint4 vop = *reinterpret_cast<const uint4 *>(sv + ((2 * e + h) * D + 32 * k + c) * 16);
+                if constexpr (kEdge)
+                    vop = make_uint4(vop.x & m01, vop.y & m23, vop.z & m45, vop.w & m67);
+                o[k] = mfma_32x32<DT>(vop, ph[e], o[k]);
+                o[k] = mfma_32x32<DT>(vop, pl[e], o[k]);
+            }
         }
     };
-    // Pipeline: while step s is computed out of one LDS buffer, the global loads
-    // of step s+1 are in flight; they are written to the other buffer after the
-    // computation, and one barrier per step orders both the hand-over of that
-    // buffer and the reuse of the current one.  Every wavefront passes the same
-    // n_steps - 1 barriers, but spends them in two loops of its own lengths: its
-    // mask-free steps first, then its edge steps (and steps past its last
-    // position, where it only copies).  The last step is peeled so that the
-    // prefetch in the loops is unconditional.
-    fetch(0);
-    deposit(0);
+
+    // Pipeline.  A step's K/V go arena -> registers -> LDS -> matrix operands.
+    // The global loads of step s+2 are issued at the top of step s (their page
+    // ids were read a step earlier still) and land in LDS at the end of step
+    // s+1, so two steps of computation cover the dependent page-id -> data
+    // latency; the LDS buffers alternate, and the one barrier per step orders
+    // both the hand-over of the buffer just written and the reuse of the one
+    // just read.  The two register sets alternate as well, which is why the
+    // loops below take two steps per trip.  Every wavefront passes n_steps
+    // barriers, but spends them in two loops of its own lengths: its mask-free
+    // steps first (an even number of them), then its edge steps and the steps
+    // past its last position, where it only copies.
+    Staged set_a, set_b;
+    int pa, pbb;
+    page_ids(0, pa, pbb);
+    fetch(set_a, pa, pbb);
+    page_ids(1, pa, pbb);
+    fetch(set_b, pa, pbb);
+    page_ids(2, pa, pbb);
+    deposit(set_a, 0);
     // Everything loaded so far (q included) has arrived before the loops start:
     // otherwise the wait counters inside them must allow for q still being in
     // flight, which in steady state means waiting for the prefetch just issued.
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
+    // one step: `mine` is free (its content went to LDS a step ago) and takes
+    // step s+2; `other` holds step s+1 and is written out after the computation
+    auto advance = [&](int s, Staged &mine, const Staged &other, auto edge) {
+        fetch(mine, pa, pbb);
+        page_ids(s + 3, pa, pbb);
+        if (!decltype(edge)::value || s <= s_last)
+            process_step(s, s & 1, edge);
+        deposit(other, (s + 1) & 1);
+        __syncthreads();
+    };
     int s = 0;
-    for (const int s_end = min(n_plain, n_steps - 1); s < s_end; ++s) {
-        fetch(s + 1);
-        process_step(s, s & 1, std::false_type{});
-        deposit((s + 1) & 1);
-        __syncthreads();
+    for (const int s_end = min(n_plain, n_steps) & ~1; s < s_end; s += 2) {
+        advance(s, set_a, set_b, std::false_type{});
+        advance(s + 1, set_b, set_a, std::false_type{});
     }
-    for (; s + 1 < n_steps; ++s) {
-        fetch(s + 1);
-        if (s <= s_last)
-            process_step(s, s & 1, std::true_type{});
-        deposit((s + 1) & 1);
-        __syncthreads();
+    for (; s < n_steps; s += 2) {
+        advance(s, set_a, set_b, std::true_type{});
+        if (s + 1 < n_steps)
+            advance(s + 1, set_b, set_a, std::true_type{});
     }
-    if (s <= s_last)
-        process_step(s, s & 1, std::true_type{});
 
-    // o[t][k][j] is dim 16k + 4g + j of row c
-#pragma unroll
-    for (int t = 0; t < NT; ++t) {
-        float l_all = l_part[t] + __shfl_xor(l_part[t], 16);
-        l_all += __shfl_xor(l_all, 32);
-        if (!active || !valid[t])
-            continue;
+    // o[k][r] is dim 32k + 8*(r/4) + 4h + r%4 of row c
+    const float l_all = l_part + __shfl_xor(l_part, 32);
+    if (valid) {
         const float inv = 1.0f / l_all;
 #pragma unroll
-        for (int k = 0; k < ND; ++k) {
-            const int64_t idx = row_off[t] + 16 * k + 4 * g;
-            const float x0 = o[t][k][0] * inv, x1 = o[t][k][1] * inv, x2 = o[t][k][2] * inv,
-                        x3 = o[t][k][3] * inv;
-            if constexpr (ODT == RLHF_F32)
-                *(float4 *)((float *)out + idx) = make_float4(x0, x1, x2, x3);
-            else
-                *(uint2 *)((uint16_t *)out + idx) =
-                    make_uint2((uint32_t)pack16<ODT>(x0) | ((uint32_t)pack16<ODT>(x1) << 16),
-                               (uint32_t)pack16<ODT>(x2) | ((uint32_t)pack16<ODT>(x3) << 16));
-        }
+        for (int k = 0; k < ND; ++k)
+#pragma unroll
+            for (int qd = 0; qd < 4; ++qd) {
+                const int64_t idx = row_off + 32 * k + 8 * qd + 4 * h;
+                const float x0 = o[k][4 * qd] * inv, x1 = o[k][4 * qd + 1] * inv, x2 = o[k][4 * qd + 2] * inv,
+                            x3 = o[k][4 * qd + 3] * inv;
+                if constexpr (ODT == RLHF_F32)
+                    *(float4 *)((float *)out + idx) = make_float4(x0, x1, x2, x3);
+                else
+                    *(uint2 *)((uint16_t *)out + idx) =
+                        make_uint2((uint32_t)pack16<ODT>(x0) | ((uint32_t)pack16<ODT>(x1) << 16),
+                                   (uint32_t)pack16<ODT>(x2) | ((uint32_t)pack16<ODT>(x3) << 16));
+            }
     }
 }
 
