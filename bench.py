@@ -34,10 +34,13 @@ METRIC = "decode-attn HBM GB/s (% of MI355X peak) + logprob/KL tokens/sec, 1 GPU
 PMC_TRAFFIC = {
     "logprob_kl": {"sources": ["logprob_kl.hip", "device_ops.h"],
                    "sha256": "deef495df77db1122d46065078daa6de157d2779e3dd3efc06e8985e2b872b76",
-                   "bytes": 67248646305 + 8854864},
-    "decode_attn": {"sources": ["attention.hip", "device_ops.h"],
-                    "sha256": "5bd47e18145ad137845588b26f598a394a634db6a42112262be155b25d932de0",
-                    "bytes": 1605410299 + 12763824 + 13416133 + 2097152},
+                   "bytes": 67249682659 + 8974752},
+    "decode_attn": {"sources": ["attention.hip", "mfma_ops.h", "device_ops.h"],
+                    "sha256": "c8308d2fa79b74c7ecdea61ad99a521c750911a188cd6c6335865c054aa81af5",
+                    "bytes": 1605399240 + 12761584 + 13416413 + 2097152},
+    "prefill_attn": {"sources": ["prefill.hip", "mfma_ops.h", "device_ops.h"],
+                     "sha256": "f3527625a8bbc7d4e311ddd0cf3a8bf13f4c0152c89a9bb16fcd5302d025484c",
+                     "bytes": 4043920698 + 3129964827},
 }
 
 
@@ -214,6 +217,59 @@ def measure(cfg, K, W, dev):
     return res
 
 
+MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f16": 2500.0}   # MI355X dense matrix-core peak
+
+
+def measure_prefill(cfg, dev, reps=5):
+    """The prefill step of the same configuration (outside the timed decode
+    step): every sequence's prompt is appended to an empty arena in one call and
+    its causal attention runs over the arena.  Returns times and flop counts."""
+    import torch
+    from paper_2410_15651_amd import binding as rb
+    from paper_2410_15651_amd import workloads as wl
+    P = wl.PAGE_TOKENS
+    lens = wl.prompt_lengths(cfg)
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    T = int(cu[-1])
+    _, ks, vs = wl.qkv(cfg, lens, device=dev)
+    k_new, v_new = torch.cat(ks).contiguous(), torch.cat(vs).contiguous()
+    del ks, vs
+    q = wl.query_rows(cfg, T, device=dev)
+    out = torch.empty_like(q)
+    cu_d = torch.from_numpy(cu).to(dev)
+    mpps = int((lens.max() + P - 1) // P)
+    n_pages = int(((lens.astype(np.int64) + P - 1) // P).sum()) + 8
+    kw = dict(max_seqs=cfg.batch, n_kv_heads=cfg.n_kv_heads, head_dim=cfg.head_dim, n_pages=n_pages,
+              max_pages_per_seq=mpps, kv_dtype=wl.DTYPE_CODE[cfg.kv_dtype],
+              initial_free_order=wl.free_order(cfg, n_pages))
+    nbytes = rb.rlhf_kv_arena_bytes_required(**kw)
+    buf = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    arena = rb.rlhf_kv_arena_create(device_buffer=buf, device_buffer_bytes=nbytes, **kw)
+    k_arena, v_arena, d_table, d_lens = rb.rlhf_kv_arena_views(arena)
+    params = rb.attn_params(cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, mpps,
+                            wl.DTYPE_CODE[cfg.kv_dtype])
+    ids = np.arange(cfg.batch, dtype=np.int32)
+    max_q = int(lens.max())
+    t_app, t_att = [], []
+    for it in range(reps + 1):
+        rb.rlhf_kv_arena_reset(arena)
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        e[0].record()
+        rb.rlhf_kv_arena_append(arena, ids, lens, k_new, v_new)
+        e[1].record()
+        rb.rlhf_prefill_attention(params, q, cu_d, max_q, k_arena, v_arena, d_table, d_lens, out)
+        e[2].record()
+        torch.cuda.synchronize()
+        if it:                      # the first pass is the warm-up
+            t_app.append(e[0].elapsed_time(e[1]) * 1e-3)
+            t_att.append(e[1].elapsed_time(e[2]) * 1e-3)
+    rb.rlhf_kv_arena_destroy(arena)
+    L = lens.astype(np.float64)
+    flops = 4.0 * cfg.head_dim * cfg.n_q_heads * float((L * (L + 1) / 2).sum())   # q.K and P.V, causal
+    return dict(rows=T, flops=flops, attn_s=float(np.mean(t_att)), append_s=float(np.mean(t_app)),
+                lens_lo=int(lens.min()), lens_hi=int(lens.max()))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -295,6 +351,21 @@ def main():
     del wk, m
     torch.cuda.empty_cache()
 
+    # the prefill step of the same workload: reported beside the decode step, not part of `value`
+    pf = measure_prefill(cfg, dev)
+    tfl = pf["flops"] / pf["attn_s"] / 1e12
+    peak = MFMA_PEAK_TFLOPS[cfg.kv_dtype]
+    result["components"].update({
+        "prefill_attn_us": round(pf["attn_s"] * 1e6, 1), "prefill_attn_TFLOPs": round(tfl, 1),
+        "prefill_append_us": round(pf["append_s"] * 1e6, 1), "prefill_rows": pf["rows"],
+        "prefill_tokens_per_s": round(pf["rows"] / (pf["attn_s"] + pf["append_s"]), 1),
+        "prefill_prompt_lengths": f"U[{max(1, cfg.len_lo // 2)},{max(1, cfg.len_hi // 2)}]"})
+    result["roofline_prefill_attn"] = {
+        "kernel": "prefill_attn_kernel", "bound": "mfma", "achieved": round(tfl, 1), "peak": peak,
+        "unit": "TFLOP/s", "frac": round(tfl / peak, 4), "traffic": measured_traffic("prefill_attn", cfg.index),
+        "flops": "4 * head_dim * q heads * sum L(L+1)/2: q.K and P.V of the causal triangle"}
+    torch.cuda.empty_cache()
+
     if not args.no_other_configs:
         others = []
         for c in wl.CONFIGS:
@@ -315,6 +386,11 @@ def main():
                 "step_GBps": round(o["value"], 1)})
             o["wk"].close()
             del o
+            torch.cuda.empty_cache()
+            pf = measure_prefill(c, dev, reps=3)
+            others[-1].update({"prefill_attn_us": round(pf["attn_s"] * 1e6, 1),
+                               "prefill_attn_TFLOPs": round(pf["flops"] / pf["attn_s"] / 1e12, 1),
+                               "prefill_append_us": round(pf["append_s"] * 1e6, 1), "prefill_rows": pf["rows"]})
             torch.cuda.empty_cache()
         result["other_configs"] = others
     print(json.dumps(result), flush=True)

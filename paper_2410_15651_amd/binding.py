@@ -84,6 +84,11 @@ def lib() -> ctypes.CDLL:
             raise FileNotFoundError(
                 f"{LIB_PATH} is missing: build it with `python -m paper_2410_15651_amd.build` "
                 "(there is no fallback path)")
+        # PyTorch carries its own copy of the HIP runtime.  Device memory comes from
+        # torch, so its runtime must be the one this process uses: load it first,
+        # and the library below binds to the runtime already present.  (Loaded the
+        # other way round, two runtimes coexist and this one finds no device.)
+        import torch  # noqa: F401
         L = ctypes.CDLL(LIB_PATH)
         vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
         P = ctypes.POINTER
