@@ -17,6 +17,7 @@ import subprocess
 
 import numpy as np
 
+from .alloc_model import CachingAllocatorModel  # noqa: F401
 from .arena_model import ArenaModel, ArenaModelError  # noqa: F401
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
