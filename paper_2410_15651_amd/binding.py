@@ -29,7 +29,16 @@ EXPORTS = [
     "rlhf_decode_attention_workspace_bytes", "rlhf_decode_attention", "rlhf_token_logprobs_kl",
     "rlhf_token_logprobs_kl_rewards", "rlhf_sample_tokens", "rlhf_prefill_attention",
     "rlhf_last_error_string", "rlhf_version",
+    "rlhf_alloc_sim_create", "rlhf_alloc_sim_destroy", "rlhf_alloc_sim_malloc", "rlhf_alloc_sim_free",
+    "rlhf_alloc_sim_empty_cache", "rlhf_alloc_sim_stats",
 ]
+
+
+class AllocSimStats(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_uint64) for n in (
+        "reserved_bytes", "allocated_bytes", "peak_reserved_bytes", "peak_allocated_bytes",
+        "driver_allocations", "driver_frees", "last_fragmentation_bytes", "peak_fragmentation_bytes",
+        "fragmentation_at_peak_reserved_bytes", "n_segments", "n_free_blocks")]
 
 
 class RlhfError(RuntimeError):
@@ -110,6 +119,13 @@ def lib() -> ctypes.CDLL:
         L.rlhf_sample_tokens.argtypes = [vp, vp, vp, i64, i32, i64, i32, ctypes.c_float, ctypes.c_uint64,
                                          ctypes.c_uint64, vp]
         L.rlhf_prefill_attention.argtypes = [P(AttnParams), vp, vp, i32, vp, vp, vp, vp, vp, vp]
+        u64 = ctypes.c_uint64
+        L.rlhf_alloc_sim_create.argtypes = [P(vp)]
+        L.rlhf_alloc_sim_destroy.argtypes = [vp]
+        L.rlhf_alloc_sim_malloc.argtypes = [vp, u64, P(u64)]
+        L.rlhf_alloc_sim_free.argtypes = [vp, u64]
+        L.rlhf_alloc_sim_empty_cache.argtypes = [vp]
+        L.rlhf_alloc_sim_stats.argtypes = [vp, P(AllocSimStats)]
         L.rlhf_last_error_string.restype = ctypes.c_char_p
         L.rlhf_last_error_string.argtypes = []
         L.rlhf_version.argtypes = []
@@ -321,3 +337,40 @@ def rlhf_last_error_string() -> str:
 
 def rlhf_version() -> int:
     return lib().rlhf_version()
+
+
+# ------------------------------------------------- allocator simulator ----
+class AllocSim:
+    """The library's caching-allocator simulator (include/rlhf_memtrace.h)."""
+
+    def __init__(self):
+        h = ctypes.c_void_p()
+        _check(lib().rlhf_alloc_sim_create(ctypes.byref(h)))
+        self._h = h
+
+    def malloc(self, nbytes: int) -> int:
+        out = ctypes.c_uint64()
+        _check(lib().rlhf_alloc_sim_malloc(self._h, int(nbytes), ctypes.byref(out)))
+        return out.value
+
+    def free(self, handle: int) -> None:
+        _check(lib().rlhf_alloc_sim_free(self._h, int(handle)))
+
+    def empty_cache(self) -> None:
+        _check(lib().rlhf_alloc_sim_empty_cache(self._h))
+
+    def stats(self) -> dict:
+        st = AllocSimStats()
+        _check(lib().rlhf_alloc_sim_stats(self._h, ctypes.byref(st)))
+        return {n: getattr(st, n) for n, _ in AllocSimStats._fields_}
+
+    def close(self) -> None:
+        if self._h:
+            lib().rlhf_alloc_sim_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -15,7 +15,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librlhf_rollout.so")
-SOURCES = ["error.cpp", "arena.hip", "attention.hip", "logprob_kl.hip", "sampling.hip", "prefill.hip"]
+SOURCES = ["error.cpp", "alloc_sim.cpp", "arena.hip", "attention.hip", "logprob_kl.hip", "sampling.hip", "prefill.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 FLAGS = [
@@ -37,6 +37,7 @@ def is_stale() -> bool:
     t = os.path.getmtime(LIB)
     deps = [os.path.join(CSRC, f) for f in os.listdir(CSRC)]
     deps.append(os.path.join(ROOT, "include", "rlhf_rollout.h"))
+    deps.append(os.path.join(ROOT, "include", "rlhf_memtrace.h"))
     return any(os.path.getmtime(d) > t for d in deps)
 
 

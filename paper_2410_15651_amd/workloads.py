@@ -240,3 +240,137 @@ def plain_pages(ks, vs, page_table: np.ndarray, n_pages: int):
             kp[page, :, : t1 - t0, :] = np.swapaxes(k[t0:t1], 0, 1)
             vp[page, :, : t1 - t0, :] = np.swapaxes(v[t0:t1], 0, 1)
     return kp, vp
+
+
+# ---------------------------------------------------------------------------
+# Allocation trace of one PPO iteration (Section 2.1: generation, then the
+# actor / reference / critic / reward inferences, then actor and critic
+# training).  Only tensor sizes and lifetimes are stated here -- the order in
+# which a framework built on an eager tensor library asks its allocator for
+# memory -- no allocator policy.  Events:
+#   ("phase", name) | ("alloc", key, nbytes, kind) | ("free", key)
+# kind is "kv" for the key/value cache of generation and "tensor" otherwise.
+@dataclass(frozen=True)
+class TraceShape:
+    name: str
+    n_layers: int
+    hidden: int
+    n_kv_heads: int
+    head_dim: int
+    vocab: int
+    critic_layers: int
+    critic_hidden: int
+    batch: int
+    prompt_len: int
+    gen_len: int
+    lora_rank: int = 128
+
+
+TRACE_SHAPES = {
+    # actor/reference OPT-1.3b-shaped, critic/reward OPT-350m-shaped, the paper's batch of 2 (Section 3)
+    "opt1.3b_b2": TraceShape("opt1.3b_b2", 24, 2048, 32, 64, 50272, 24, 1024, 2, 256, 256),
+    # the same models at a rollout batch of 32 (the other framework's setting in Section 3)
+    "opt1.3b_b32": TraceShape("opt1.3b_b32", 24, 2048, 32, 64, 50272, 24, 1024, 32, 256, 256),
+}
+
+
+def ppo_iteration_trace(shape: TraceShape, iterations: int = 2, seed: int = BASE_SEED):
+    """Events of `iterations` PPO iterations.  Prompts are padded to a length
+    drawn per iteration from [prompt_len/2, prompt_len], so successive
+    iterations ask for slightly different sizes, as real batches do."""
+    rng = _cpu_rng(seed, 8)
+    ev = []
+    counter = [0]
+
+    def alloc(nbytes, kind="tensor"):
+        counter[0] += 1
+        ev.append(("alloc", counter[0], int(nbytes), kind))
+        return counter[0]
+
+    def free(key):
+        ev.append(("free", key))
+
+    B, NL, Hd, V = shape.batch, shape.n_layers, shape.hidden, shape.vocab
+    kv_row = shape.n_kv_heads * shape.head_dim * 2            # bytes of one token's K (or V) in one layer
+    # persistent: LoRA adapters, their gradients and optimizer moments (fp32), actor and critic
+    ev.append(("phase", "setup"))
+    for layers, hid in ((NL, Hd), (shape.critic_layers, shape.critic_hidden)):
+        for _ in range(layers):
+            for _ in range(4):                                 # adapter, gradient, two moments
+                alloc(2 * hid * shape.lora_rank * 4 * 4)       # four adapted projections, A and B halves
+    for it in range(iterations):
+        P0 = int(rng.integers(max(1, shape.prompt_len // 2), shape.prompt_len + 1))
+        G = shape.gen_len
+        S = P0 + G
+        # ---- generation: the cache of every layer grows by concatenation each step
+        ev.append(("phase", f"generation[{it}]"))
+        cache = [(alloc(B * P0 * kv_row, "kv"), alloc(B * P0 * kv_row, "kv")) for _ in range(NL)]
+        ids = alloc(B * S * 8)
+        for t in range(1, G + 1):
+            h = alloc(B * Hd * 2)
+            for layer in range(NL):
+                k_new, v_new = alloc(B * (P0 + t) * kv_row, "kv"), alloc(B * (P0 + t) * kv_row, "kv")
+                free(cache[layer][0])
+                free(cache[layer][1])
+                cache[layer] = (k_new, v_new)
+                h2 = alloc(B * Hd * 2)
+                free(h)
+                h = h2
+            logits = alloc(B * V * 4)
+            probs = alloc(B * V * 4)
+            free(logits)
+            free(probs)
+            free(h)
+        for k_c, v_c in cache:
+            free(k_c)
+            free(v_c)
+        # ---- four inferences over the full sequences
+        outputs = []
+        for who, layers, hid, head in (("actor", NL, Hd, V), ("reference", NL, Hd, V),
+                                       ("critic", shape.critic_layers, shape.critic_hidden, 1),
+                                       ("reward", shape.critic_layers, shape.critic_hidden, 1)):
+            ev.append(("phase", f"inference:{who}[{it}]"))
+            h = alloc(B * S * hid * 2)
+            for _ in range(layers):
+                att = alloc(B * S * hid * 2 * 3)               # fused q, k, v projections
+                h2 = alloc(B * S * hid * 2)
+                mlp = alloc(B * S * hid * 4 * 2)
+                free(att)
+                free(h)
+                free(mlp)
+                h = h2
+            out = alloc(B * S * head * 2)
+            free(h)
+            if head > 1:
+                lsm = alloc(B * S * head * 4)                  # fp32 log-softmax
+                free(out)
+                out = alloc(B * S * 4)                         # gathered log-probs
+                free(lsm)
+            outputs.append(out)
+        # ---- training: actor, then critic; activations kept for backward, freed in reverse
+        for who, layers, hid, head in (("actor", NL, Hd, V), ("critic", shape.critic_layers, shape.critic_hidden, 1)):
+            ev.append(("phase", f"training:{who}[{it}]"))
+            saved = []
+            h = alloc(B * S * hid * 2)
+            for _ in range(layers):
+                saved.append(alloc(B * S * hid * 2))            # checkpointed layer input
+                tmp = alloc(B * S * hid * 4 * 2)
+                free(tmp)
+            out = alloc(B * S * head * 4)
+            grad_out = alloc(B * S * head * 4)
+            free(out)
+            for s_ in reversed(saved):
+                re1 = alloc(B * S * hid * 2 * 3)                # recomputation + gradient temporaries
+                re2 = alloc(B * S * hid * 4 * 2)
+                g = alloc(B * S * hid * 2)
+                free(re1)
+                free(re2)
+                free(s_)
+                free(g)
+            free(grad_out)
+            free(h)
+        for o in outputs:
+            free(o)
+        free(ids)
+    ev.append(("phase", "end"))
+    return ev

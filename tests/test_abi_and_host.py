@@ -18,14 +18,15 @@ P = 16
 
 
 def _declared_functions():
-    text = open(os.path.join(ROOT, "include", "rlhf_rollout.h")).read()
+    text = "".join(open(os.path.join(ROOT, "include", f)).read()
+                   for f in sorted(os.listdir(os.path.join(ROOT, "include"))) if f.endswith(".h"))
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(rlhf_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_library_exports_every_declared_function():
     names = _declared_functions()
-    assert len(names) >= 18
+    assert len(names) >= 24
     L = ctypes.CDLL(rb.LIB_PATH)
     for n in names:
         assert hasattr(L, n), n

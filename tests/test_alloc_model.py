@@ -105,3 +105,43 @@ def test_invariants_on_random_traces(ops):
     s = m.stats()
     assert s["reserved_bytes"] == 0 and s["allocated_bytes"] == 0 and s["n_segments"] == 0
     assert s["driver_frees"] == s["driver_allocations"]
+
+
+# ---- the library's simulator against the model, counter by counter ----------
+def _lib_model():
+    from paper_2410_15651_amd import binding as rb
+    return rb.AllocSim
+
+
+@pytest.mark.parametrize("name", sorted(hand_traces()))
+def test_library_simulator_on_hand_worked_traces(name):
+    for step, (expect, got) in enumerate(replay(_lib_model(), hand_traces()[name])):
+        assert got == expect, (name, step)
+
+
+@settings(max_examples=150, deadline=None)
+@given(st.lists(st.tuples(st.sampled_from(["m", "m", "m", "f", "f", "e"]),
+                          st.one_of(st.integers(1, 4096), st.integers(1, 3 << 20), st.integers(1, 40 << 20)),
+                          st.integers(0, 1000)), max_size=200))
+def test_library_simulator_matches_model_on_random_traces(ops):
+    from paper_2410_15651_amd import binding as rb
+    lib_sim, model = rb.AllocSim(), CachingAllocatorModel()
+    live = []
+    try:
+        for op, size, pick in ops:
+            if op == "m":
+                live.append((lib_sim.malloc(size), model.malloc(size)))
+            elif op == "f" and live:
+                a, b = live.pop(pick % len(live))
+                lib_sim.free(a)
+                model.free(b)
+            elif op == "e":
+                lib_sim.empty_cache()
+                model.empty_cache()
+            assert lib_sim.stats() == model.stats()
+        with pytest.raises(rb.RlhfError):
+            lib_sim.free(10 ** 9)
+        with pytest.raises(rb.RlhfError):
+            lib_sim.malloc(0)
+    finally:
+        lib_sim.close()
