@@ -12,7 +12,8 @@
 // device mirrors and three small kernels:
 //   arena_apply_kernel    applies one call's page-table / length changes, read
 //                         straight from a pinned command slot
-//   kv_scatter_kernel     writes new K/V rows into their pages in block layout
+//   kv_scatter_kernel /   write new K/V rows into their pages in block layout
+//   kv_scatter_pages_kernel   (token by token / a whole page at a time)
 //   kv_gather_kernel      reads rows back in plain [token][head][dim] order
 #include <hip/hip_runtime.h>
 
@@ -30,10 +31,12 @@ namespace {
 
 constexpr int kRingSlots = 4;
 constexpr int kPage = RLHF_PAGE_TOKENS;
+constexpr int kDescWords = 6;
 
 // Command slot layout (int32 words):
 //   [0] n_desc  [1] n_table  [2] n_lens  [3] unused
-//   desc [n_desc][4]  = token_offset, seq, start_len, n_new      (non-empty sequences only)
+//   desc [n_desc][6]  = token_offset, seq, start_len, n_new, whole pages before this entry,
+//                       edge tokens before this entry            (non-empty sequences only)
 //   table[n_table][2] = table_index, page (or -1)
 //   lens [n_lens][2]  = seq, new_len
 __global__ void arena_apply_kernel(const int32_t *__restrict__ cmd, int32_t *__restrict__ table,
@@ -41,11 +44,11 @@ __global__ void arena_apply_kernel(const int32_t *__restrict__ cmd, int32_t *__r
 {
     const int n_desc = cmd[0], n_table = cmd[1], n_lens = cmd[2];
     const int32_t *c_desc = cmd + 4;
-    const int32_t *c_table = c_desc + 4 * n_desc;
+    const int32_t *c_table = c_desc + kDescWords * n_desc;
     const int32_t *c_lens = c_table + 2 * n_table;
     const int stride = gridDim.x * blockDim.x;
     const int tid = blockIdx.x * blockDim.x + threadIdx.x;
-    for (int i = tid; i < 4 * n_desc; i += stride)
+    for (int i = tid; i < kDescWords * n_desc; i += stride)
         desc[i] = c_desc[i];
     for (int i = tid; i < n_table; i += stride)
         table[c_table[2 * i]] = c_table[2 * i + 1];
@@ -70,31 +73,47 @@ __device__ __forceinline__ int v_block_offset(int slot, int d, int head_dim)
     return ((slot >> 2) * head_dim + d) * 4 + (slot & 3);
 }
 
-// One wavefront per (new token, kv head).
-__global__ __launch_bounds__(256) void kv_scatter_kernel(
-    const uint16_t *__restrict__ k_new, const uint16_t *__restrict__ v_new,
-    uint16_t *__restrict__ k_arena, uint16_t *__restrict__ v_arena,
-    const int32_t *__restrict__ table, const int32_t *__restrict__ desc, int n_desc,
-    int64_t total_tokens, int n_kv_heads, int head_dim, int mpps)
+// An append splits each sequence's new tokens into the pages they fill
+// completely and the "edge" tokens before and after those (a decode step is all
+// edge tokens, a prompt nearly all whole pages).
+//
+// Last descriptor whose word `field` is <= x.
+__device__ __forceinline__ int find_desc(const int32_t *__restrict__ desc, int n_desc, int field, int64_t x)
 {
-    const int lane = threadIdx.x & 63;
-    const int64_t item = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (item >= total_tokens * n_kv_heads)
-        return;
-    const int64_t t = item / n_kv_heads;
-    const int h = (int)(item - t * n_kv_heads);
-    // last descriptor whose token_offset <= t
     int lo = 0, hi = n_desc - 1;
     while (lo < hi) {
         const int mid = (lo + hi + 1) >> 1;
-        if (desc[4 * mid] <= t)
+        if (desc[kDescWords * mid + field] <= x)
             lo = mid;
         else
             hi = mid - 1;
     }
-    const int seq = desc[4 * lo + 1];
-    const int pos = desc[4 * lo + 2] + (int)(t - desc[4 * lo]);
-    const int page = table[(int64_t)seq * mpps + pos / kPage];
+    return lo;
+}
+
+// Edge tokens: one wavefront per (token, kv head); K goes in 16-byte granules,
+// V element by element into its transposed granules.
+__global__ __launch_bounds__(256) void kv_scatter_kernel(
+    const uint16_t *__restrict__ k_new, const uint16_t *__restrict__ v_new,
+    uint16_t *__restrict__ k_arena, uint16_t *__restrict__ v_arena,
+    const int32_t *__restrict__ table, const int32_t *__restrict__ desc, int n_desc,
+    int64_t edge_tokens, int n_kv_heads, int head_dim, int mpps)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t item = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (item >= edge_tokens * n_kv_heads)
+        return;
+    const int64_t e = item / n_kv_heads;
+    const int h = (int)(item - e * n_kv_heads);
+    const int32_t *d = desc + kDescWords * find_desc(desc, n_desc, 5, e);
+    const int start = d[2], n_new = d[3];
+    const int first_whole = (start + kPage - 1) / kPage * kPage;         // position where whole pages begin
+    const int head_count = min(first_whole - start, n_new);              // edge tokens in front of them
+    const int whole_end = head_count < n_new ? (start + n_new) / kPage * kPage : first_whole;
+    const int e_local = (int)(e - d[5]);
+    const int pos = e_local < head_count ? start + e_local : max(whole_end, first_whole) + (e_local - head_count);
+    const int64_t t = (int64_t)d[0] + (pos - start);
+    const int page = table[(int64_t)d[1] * mpps + pos / kPage];
     const int slot = pos % kPage;
     const int64_t block = ((int64_t)page * n_kv_heads + h) * (kPage * head_dim);
     const int64_t src = (t * n_kv_heads + h) * head_dim;
@@ -106,6 +125,54 @@ __global__ __launch_bounds__(256) void kv_scatter_kernel(
         const uint32_t w = *(const uint32_t *)(v_new + src + lane * 2);
         v_arena[block + v_block_offset(slot, lane * 2, head_dim)] = (uint16_t)(w & 0xffffu);
         v_arena[block + v_block_offset(slot, lane * 2 + 1, head_dim)] = (uint16_t)(w >> 16);
+    }
+}
+
+// Whole pages: one wavefront per (page, kv head) writes the 16 tokens' K block
+// and V block with full 16-byte stores.  K: a block granule is 8 dims of one
+// token, copied as it is.  V: a lane takes two adjacent dims of the four tokens
+// of a slot quad (four coalesced 4-byte loads) and writes the two transposed
+// granules side by side.
+__global__ __launch_bounds__(256) void kv_scatter_pages_kernel(
+    const uint16_t *__restrict__ k_new, const uint16_t *__restrict__ v_new,
+    uint16_t *__restrict__ k_arena, uint16_t *__restrict__ v_arena,
+    const int32_t *__restrict__ table, const int32_t *__restrict__ desc, int n_desc,
+    int64_t whole_pages, int n_kv_heads, int head_dim, int mpps)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t item = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (item >= whole_pages * n_kv_heads)
+        return;
+    const int64_t pg = item / n_kv_heads;
+    const int h = (int)(item - pg * n_kv_heads);
+    const int32_t *d = desc + kDescWords * find_desc(desc, n_desc, 4, pg);
+    const int start = d[2];
+    const int lp = (start + kPage - 1) / kPage + (int)(pg - d[4]);      // logical page of the sequence
+    const int64_t t0 = (int64_t)d[0] + ((int64_t)lp * kPage - start);    // its first token in k_new / v_new
+    const int page = table[(int64_t)d[1] * mpps + lp];
+    const int64_t block = ((int64_t)page * n_kv_heads + h) * (kPage * head_dim);
+    const int64_t row = (int64_t)n_kv_heads * head_dim;                  // elements between two tokens
+    const int64_t src = (t0 * n_kv_heads + h) * head_dim;
+    // K: granule g = (dim/8)*16 + slot
+    for (int g = lane; g < 2 * head_dim; g += 64) {
+        const int slot = g & 15, d8 = g >> 4;
+        *(uint4 *)(k_arena + block + g * 8) = *(const uint4 *)(k_new + src + slot * row + d8 * 8);
+    }
+    // V: lane = pair of dims; granules (quad, dim) and (quad, dim+1) are adjacent
+    if (lane < head_dim / 2) {
+#pragma unroll
+        for (int quad = 0; quad < 4; ++quad) {
+            uint32_t w[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                w[j] = *(const uint32_t *)(v_new + src + (4 * quad + j) * row + lane * 2);
+            uint4 out;
+            out.x = (w[0] & 0xffffu) | (w[1] << 16);
+            out.y = (w[2] & 0xffffu) | (w[3] << 16);
+            out.z = (w[0] >> 16) | (w[1] & 0xffff0000u);
+            out.w = (w[2] >> 16) | (w[3] & 0xffff0000u);
+            *(uint4 *)(v_arena + block + (quad * head_dim + lane * 2) * 4) = out;
+        }
     }
 }
 
@@ -299,8 +366,8 @@ extern "C" int rlhf_kv_arena_create(const rlhf_kv_arena_desc *desc, rlhf_kv_aren
     const size_t table_elems = (size_t)desc->max_seqs * desc->max_pages_per_seq;
     ARENA_TRY(hipMalloc((void **)&a->d_table, table_elems * sizeof(int32_t)));
     ARENA_TRY(hipMalloc((void **)&a->d_lens, (size_t)desc->max_seqs * sizeof(int32_t)));
-    ARENA_TRY(hipMalloc((void **)&a->d_desc, (size_t)desc->max_seqs * 4 * sizeof(int32_t)));
-    a->slot_words = 4 + 6 * (size_t)desc->max_seqs + 2 * (size_t)desc->n_pages;
+    ARENA_TRY(hipMalloc((void **)&a->d_desc, (size_t)desc->max_seqs * kDescWords * sizeof(int32_t)));
+    a->slot_words = 4 + (kDescWords + 2) * (size_t)desc->max_seqs + 2 * (size_t)desc->n_pages;
     for (auto &s : a->ring) {
         ARENA_TRY(hipHostMalloc((void **)&s.host, a->slot_words * sizeof(int32_t), hipHostMallocDefault));
         ARENA_TRY(hipEventCreateWithFlags(&s.done, hipEventDisableTiming));
@@ -362,42 +429,59 @@ extern "C" int rlhf_kv_arena_append(rlhf_kv_arena *arena, const int32_t *seq_ids
     int32_t *w = slot->host;
     int n_desc = 0;
     int32_t *w_desc = w + 4;
+    int64_t whole_pages = 0, edge_tokens = 0;
     for (const auto &e : plan.seqs) {
         if (e.n_new == 0)
             continue;
-        w_desc[4 * n_desc + 0] = e.token_offset;
-        w_desc[4 * n_desc + 1] = e.seq;
-        w_desc[4 * n_desc + 2] = e.start_len;
-        w_desc[4 * n_desc + 3] = e.n_new;
+        int32_t *d = w_desc + kDescWords * n_desc;
+        d[0] = e.token_offset;
+        d[1] = e.seq;
+        d[2] = e.start_len;
+        d[3] = e.n_new;
+        d[4] = (int32_t)whole_pages;
+        d[5] = (int32_t)edge_tokens;
+        const int first_whole = (e.start_len + kPage - 1) / kPage;      // first page the entry may fill alone
+        const int end_whole = (e.start_len + e.n_new) / kPage;           // one past the last it fills
+        const int n_whole = std::max(0, end_whole - first_whole);
+        whole_pages += n_whole;
+        edge_tokens += e.n_new - n_whole * kPage;
         ++n_desc;
     }
-    int32_t *w_table = w_desc + 4 * n_desc;
+    int32_t *w_table = w_desc + kDescWords * n_desc;
     for (size_t i = 0; i < plan.new_pages.size(); ++i) {
         w_table[2 * i] = plan.new_pages[i].table_index;
         w_table[2 * i + 1] = plan.new_pages[i].page;
     }
     int32_t *w_lens = w_table + 2 * plan.new_pages.size();
     for (int i = 0; i < n_desc; ++i) {
-        w_lens[2 * i] = w_desc[4 * i + 1];
-        w_lens[2 * i + 1] = w_desc[4 * i + 2] + w_desc[4 * i + 3];
+        w_lens[2 * i] = w_desc[kDescWords * i + 1];
+        w_lens[2 * i + 1] = w_desc[kDescWords * i + 2] + w_desc[kDescWords * i + 3];
     }
     w[0] = n_desc;
     w[1] = (int32_t)plan.new_pages.size();
     w[2] = n_desc;
     w[3] = 0;
-    rc = submit_slot(arena, slot, std::max<int>(4 * n_desc, (int)plan.new_pages.size()), s);
+    rc = submit_slot(arena, slot, std::max<int>(kDescWords * n_desc, (int)plan.new_pages.size()), s);
     if (rc != RLHF_OK)
         return rc;
 
-    const int64_t items = plan.total_tokens * arena->desc.n_kv_heads;
-    const int64_t blocks = (items + 3) / 4;
-    if (blocks > 0x7fffffffLL)
+    const int64_t heads = arena->desc.n_kv_heads;
+    if ((whole_pages * heads + 3) / 4 > 0x7fffffffLL || (edge_tokens * heads + 3) / 4 > 0x7fffffffLL)
         return fail(RLHF_ERR_INVALID, "append too large for one launch");
-    hipLaunchKernelGGL(kv_scatter_kernel, dim3((unsigned)blocks), dim3(256), 0, s,
-                       (const uint16_t *)k_new, (const uint16_t *)v_new, (uint16_t *)arena->kv,
-                       (uint16_t *)(arena->kv + arena->half_bytes), arena->d_table, arena->d_desc, n_desc,
-                       plan.total_tokens, arena->desc.n_kv_heads, arena->desc.head_dim,
-                       arena->desc.max_pages_per_seq);
+    if (whole_pages > 0) {
+        hipLaunchKernelGGL(kv_scatter_pages_kernel, dim3((unsigned)((whole_pages * heads + 3) / 4)), dim3(256), 0, s,
+                           (const uint16_t *)k_new, (const uint16_t *)v_new, (uint16_t *)arena->kv,
+                           (uint16_t *)(arena->kv + arena->half_bytes), arena->d_table, arena->d_desc, n_desc,
+                           whole_pages, arena->desc.n_kv_heads, arena->desc.head_dim,
+                           arena->desc.max_pages_per_seq);
+        RLHF_LAUNCH_CHECK("kv_scatter_pages_kernel");
+    }
+    if (edge_tokens > 0)
+        hipLaunchKernelGGL(kv_scatter_kernel, dim3((unsigned)((edge_tokens * heads + 3) / 4)), dim3(256), 0, s,
+                           (const uint16_t *)k_new, (const uint16_t *)v_new, (uint16_t *)arena->kv,
+                           (uint16_t *)(arena->kv + arena->half_bytes), arena->d_table, arena->d_desc, n_desc,
+                           edge_tokens, arena->desc.n_kv_heads, arena->desc.head_dim,
+                           arena->desc.max_pages_per_seq);
     RLHF_LAUNCH_CHECK("kv_scatter_kernel");
     return RLHF_OK;
 }

@@ -114,6 +114,40 @@ def test_arena_append_gather_and_layout_bit_exact(gu, cfg_index, batch):
         A.close()
 
 
+@pytest.mark.parametrize("dtype,head_dim", [("bf16", 128), ("f16", 64)])
+def test_arena_appends_that_mix_edge_tokens_and_whole_pages(gu, dtype, head_dim):
+    """Calls whose tokens start or end inside a page and cover whole pages in
+    between (the append writes whole pages and edge tokens with different
+    kernels): every row read back must be the row that went in."""
+    cfg = wl.small_variant(wl.config(3), batch=4, n_q_heads=6, n_kv_heads=3, head_dim=head_dim, kv_dtype=dtype)
+    calls = [([0, 1, 2, 3], [5, 16, 0, 33]), ([1, 0, 3], [40, 59, 15]), ([2, 0], [100, 1]), ([3, 2, 1], [16, 12, 7])]
+    total = np.zeros(4, dtype=np.int64)
+    for ids, ns in calls:
+        total[ids] += ns
+    _, ks, vs = wl.qkv(cfg, total, device=gu.DEV)
+    n_pages = int(((total + P - 1) // P).sum()) + 5
+    order = np.random.default_rng(7).permutation(n_pages).astype(np.int32)
+    mpps = int((total.max() + P - 1) // P)
+    arena = rb.rlhf_kv_arena_create(max_seqs=4, n_kv_heads=3, head_dim=head_dim, n_pages=n_pages,
+                                    max_pages_per_seq=mpps, kv_dtype=wl.DTYPE_CODE[dtype], initial_free_order=order)
+    try:
+        done = np.zeros(4, dtype=np.int64)
+        for ids, ns in calls:
+            k_new = torch.cat([ks[b][done[b]:done[b] + n] for b, n in zip(ids, ns)]).contiguous()
+            v_new = torch.cat([vs[b][done[b]:done[b] + n] for b, n in zip(ids, ns)]).contiguous()
+            rb.rlhf_kv_arena_append(arena, ids, ns, k_new, v_new)
+            for b, n in zip(ids, ns):
+                done[b] += n
+        for b in range(4):
+            ko, vo = torch.zeros_like(ks[b]), torch.zeros_like(vs[b])
+            rb.rlhf_kv_arena_gather(arena, b, 0, int(total[b]), ko, vo)
+            torch.cuda.synchronize()
+            assert torch.equal(ko.view(torch.int16), ks[b].view(torch.int16)), b
+            assert torch.equal(vo.view(torch.int16), vs[b].view(torch.int16)), b
+    finally:
+        rb.rlhf_kv_arena_destroy(arena)
+
+
 # -------------------------------------------------------------- attention ----
 SMALL_ATTN = [
     # (config index, overrides) -- shapes span several pages, chunks and a ragged tail
