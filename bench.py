@@ -284,7 +284,7 @@ def main():
                          "traffic, to scale hardware byte counters in a rocprofv3 --pmc run)")
     args = ap.parse_args()
     if args.gpus != 1:
-        log("bench.py: this build runs on ONE GPU; --gpus above 1 is not supported "
+        log("bench.py: the library runs on ONE GPU; --gpus above 1 is not supported "
             "(no collectives or sharding are part of it).")
         sys.exit(2)
 
@@ -315,14 +315,14 @@ def main():
     result = {
         "metric": METRIC, "value": round(m["value"], 1), "unit": "GB/s", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": round(m["ms_per_step"], 4), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f32 accumulate (bf16/f16 storage)", "data": "synthetic",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"configs[{cfg.index - 1}] {cfg.name}: batch {cfg.batch}, {cfg.n_q_heads}q/"
                                f"{cfg.n_kv_heads}kv heads, head_dim {cfg.head_dim}, {cfg.kv_dtype} KV, cache "
                                f"lengths U[{cfg.len_lo},{cfg.len_hi}], 16-token pages "
                                f"{'shuffled' if cfg.shuffled_pages else 'in order'}; logprob/KL {n_pos} positions x "
                                f"vocab {cfg.vocab}, {cfg.logits_dtype} logits",
                    "step": "append 1 token/seq + decode attention + token logprob/KL",
-                   "accumulate": "fp32", "hbm_peak_GBps": HBM_PEAK_GBPS, "rotating_input_sets": m["n_sets"]},
+                   "storage": f"{cfg.kv_dtype} K/V, {cfg.logits_dtype} logits; fp32 arithmetic", "hbm_peak_GBps": HBM_PEAK_GBPS, "rotating_input_sets": m["n_sets"]},
         "components": {
             "decode_attn_GBps": round(m["attn_gbps"], 1),
             "decode_attn_frac_of_peak": round(m["attn_gbps"] / HBM_PEAK_GBPS, 4),
