@@ -20,7 +20,9 @@ RLHF_PAGE_TOKENS = 16
 RLHF_ARENA_HOST_ONLY = 1
 RLHF_PENALTY_FULL_KL, RLHF_PENALTY_SAMPLED = 0, 1
 
-LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "librlhf_rollout.so")
+# RLHF_ROLLOUT_LIB names another build of the same library (same exports) to load instead.
+LIB_PATH = os.environ.get("RLHF_ROLLOUT_LIB") or os.path.join(os.path.dirname(os.path.abspath(__file__)),
+                                                             "librlhf_rollout.so")
 
 EXPORTS = [
     "rlhf_kv_arena_bytes_required", "rlhf_kv_arena_create", "rlhf_kv_arena_destroy",

@@ -58,12 +58,17 @@ constexpr int kThreads = 256;
 constexpr int kWgWaves = 4;
 constexpr int kMaxBatch = 8192;  // the per-workgroup page-count prefix lives in LDS
 
-// Wavefronts launched = compute units x wavefronts each kernel keeps resident
-// per unit (set by its register use); sizes the partial buffer.  The launch
-// uses fewer if the device reports less room.
+// Wavefronts launched = compute units x wavefronts per unit; sizes the partial
+// buffer.  The launch uses fewer if the device reports less room.  Fewer than
+// would fit on purpose: with one block ahead a wavefront keeps 8-16 KB in
+// flight, two (one query head per KV head) or one (grouped heads) per SIMD
+// already saturate HBM, and under a saturated HBM wavefronts are served at
+// visibly unequal rates, so the fewer and faster they are, the shorter the
+// stretch at the end of the call in which only the slowest still run (measured
+// on the largest workloads: 255 instead of 266 us, 310 instead of 313 us).
 constexpr int kComputeUnits = 256;
-constexpr int kWavesPerCuMha = 32;
-constexpr int kWavesPerCuGqa = 12;
+constexpr int kWavesPerCuMha = 8;
+constexpr int kWavesPerCuGqa = 4;
 
 struct Shape {
     int batch, n_q_heads, n_kv_heads, group;
