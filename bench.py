@@ -34,13 +34,13 @@ METRIC = "decode-attn HBM GB/s (% of MI355X peak) + logprob/KL tokens/sec, 1 GPU
 PMC_TRAFFIC = {
     "logprob_kl": {"sources": ["logprob_kl.hip", "device_ops.h"],
                    "sha256": "deef495df77db1122d46065078daa6de157d2779e3dd3efc06e8985e2b872b76",
-                   "bytes": 67249682659 + 8974752},
+                   "bytes": 67248796934 + 9197336},
     "decode_attn": {"sources": ["attention.hip", "mfma_ops.h", "device_ops.h"],
-                    "sha256": "c8308d2fa79b74c7ecdea61ad99a521c750911a188cd6c6335865c054aa81af5",
-                    "bytes": 1605399240 + 12761584 + 13416413 + 2097152},
+                    "sha256": "66cc014f0071b48cb1d5568592032ea89776ecf42ec40852f392684dcb23eb36",
+                    "bytes": 1604485983 + 8513880 + 8987244 + 2097152},
     "prefill_attn": {"sources": ["prefill.hip", "mfma_ops.h", "device_ops.h"],
                      "sha256": "f3527625a8bbc7d4e311ddd0cf3a8bf13f4c0152c89a9bb16fcd5302d025484c",
-                     "bytes": 4043920698 + 3129964827},
+                     "bytes": 4043501057 + 3129959211},
 }
 
 
