@@ -200,11 +200,13 @@ def measure(cfg, K, W, dev):
     rows = wk.sets[0]["actor"][:cfg.batch]
     toks = torch.empty(cfg.batch, dtype=torch.int32, device=dev)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    sample_ws = torch.empty(wk.rb.rlhf_sample_tokens_workspace_bytes(cfg.batch, cfg.vocab), dtype=torch.uint8,
+                            device=dev)
     for it in range(3):
-        wk.rb.rlhf_sample_tokens(rows, toks, 1.0, cfg.seed, it)
+        wk.rb.rlhf_sample_tokens_split(rows, toks, 1.0, cfg.seed, sample_ws, it)
     e0.record()
     for it in range(20):
-        wk.rb.rlhf_sample_tokens(rows, toks, 1.0, cfg.seed, 3 + it)
+        wk.rb.rlhf_sample_tokens_split(rows, toks, 1.0, cfg.seed, sample_ws, 3 + it)
     e1.record()
     torch.cuda.synchronize()
     sample_us = e0.elapsed_time(e1) / 20 * 1e3

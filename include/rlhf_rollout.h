@@ -278,6 +278,20 @@ int rlhf_sample_tokens(const void *logits, int32_t *tokens_out, float *logp_out,
                        int32_t vocab, int64_t row_stride_elems, int32_t logits_dtype, float temperature,
                        uint64_t seed, uint64_t offset, void *stream);
 
+/* The same draw with the rows cut into segments, for calls that bring fewer rows
+ * than the chip has room for (a decode step: one row per sequence).  Each row is
+ * read by up to eight workgroups and a second small kernel merges their records;
+ * tokens_out is identical to rlhf_sample_tokens' for the same arguments (the
+ * noise depends on (row, index) only), logp_out agrees to rounding.
+ *   workspace  dev, >= rlhf_sample_tokens_workspace_bytes(n_rows, vocab),
+ *              16-byte aligned, caller-owned scratch, contents irrelevant
+ * With 512 rows or more it does what rlhf_sample_tokens does. */
+int rlhf_sample_tokens_workspace_bytes(int64_t n_rows, int32_t vocab, size_t *out_bytes);
+int rlhf_sample_tokens_split(const void *logits, int32_t *tokens_out, float *logp_out, int64_t n_rows,
+                             int32_t vocab, int64_t row_stride_elems, int32_t logits_dtype, float temperature,
+                             uint64_t seed, uint64_t offset, void *workspace, size_t workspace_bytes,
+                             void *stream);
+
 /* ------------------------------------------------------------------------
  * Prefill attention (Section 2.1: generation starts from the prompts; this is
  * the step that brings a prompt, or a chunk of it, into the cache before the

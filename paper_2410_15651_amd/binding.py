@@ -29,7 +29,8 @@ EXPORTS = [
     "rlhf_kv_arena_append", "rlhf_kv_arena_free_seq", "rlhf_kv_arena_reset", "rlhf_kv_arena_stats",
     "rlhf_kv_arena_views", "rlhf_kv_arena_host_state", "rlhf_kv_arena_gather",
     "rlhf_decode_attention_workspace_bytes", "rlhf_decode_attention", "rlhf_token_logprobs_kl",
-    "rlhf_token_logprobs_kl_rewards", "rlhf_sample_tokens", "rlhf_prefill_attention",
+    "rlhf_token_logprobs_kl_rewards", "rlhf_sample_tokens", "rlhf_sample_tokens_workspace_bytes",
+    "rlhf_sample_tokens_split", "rlhf_prefill_attention",
     "rlhf_last_error_string", "rlhf_version",
     "rlhf_alloc_sim_create", "rlhf_alloc_sim_destroy", "rlhf_alloc_sim_malloc", "rlhf_alloc_sim_free",
     "rlhf_alloc_sim_empty_cache", "rlhf_alloc_sim_stats",
@@ -120,6 +121,9 @@ def lib() -> ctypes.CDLL:
                                                      P(RewardShaping), vp]
         L.rlhf_sample_tokens.argtypes = [vp, vp, vp, i64, i32, i64, i32, ctypes.c_float, ctypes.c_uint64,
                                          ctypes.c_uint64, vp]
+        L.rlhf_sample_tokens_workspace_bytes.argtypes = [i64, i32, P(sz)]
+        L.rlhf_sample_tokens_split.argtypes = [vp, vp, vp, i64, i32, i64, i32, ctypes.c_float, ctypes.c_uint64,
+                                               ctypes.c_uint64, vp, sz, vp]
         L.rlhf_prefill_attention.argtypes = [P(AttnParams), vp, vp, i32, vp, vp, vp, vp, vp, vp]
         u64 = ctypes.c_uint64
         L.rlhf_alloc_sim_create.argtypes = [P(vp)]
@@ -331,6 +335,29 @@ def rlhf_sample_tokens(logits, tokens_out, temperature, seed, offset=0, logp_out
     _check(lib().rlhf_sample_tokens(_ptr(logits), _ptr(tokens_out), _ptr(logp_out), n_rows, vocab,
                                     row_stride_elems, logits_dtype, temperature, seed, offset,
                                     _stream(stream)))
+
+
+def rlhf_sample_tokens_workspace_bytes(n_rows: int, vocab: int) -> int:
+    out = ctypes.c_size_t()
+    _check(lib().rlhf_sample_tokens_workspace_bytes(n_rows, vocab, ctypes.byref(out)))
+    return out.value
+
+
+def rlhf_sample_tokens_split(logits, tokens_out, temperature, seed, workspace, offset=0, logp_out=None,
+                             n_rows=None, vocab=None, row_stride_elems=0, logits_dtype=None,
+                             workspace_bytes=None, stream=None) -> None:
+    if n_rows is None:
+        n_rows = logits.shape[0]
+    if vocab is None:
+        vocab = logits.shape[1]
+        row_stride_elems = logits.stride(0)
+    if logits_dtype is None:
+        logits_dtype = dtype_code(logits.dtype)
+    if workspace_bytes is None:
+        workspace_bytes = workspace.numel() * workspace.element_size()
+    _check(lib().rlhf_sample_tokens_split(_ptr(logits), _ptr(tokens_out), _ptr(logp_out), n_rows, vocab,
+                                          row_stride_elems, logits_dtype, temperature, seed, offset,
+                                          _ptr(workspace), workspace_bytes, _stream(stream)))
 
 
 def rlhf_last_error_string() -> str:

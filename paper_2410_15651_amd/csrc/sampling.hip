@@ -17,11 +17,16 @@
 // u is within 2^-6 of 1 (where a hardware log loses relative accuracy and where
 // the largest Gumbel values, the ones that decide the argmax, come from).
 //
-// One workgroup (256 or 1024 lanes) owns one row.  The pass is bound by the vector
-// ALU (ten Philox rounds per four logits plus three transcendentals per
-// logit), not by HBM: a decode step reads only batch x vocab logits.
+// One workgroup (256 or 1024 lanes) owns one row, or, when the caller brings a
+// workspace and the rows are too few to occupy the chip, one of up to eight
+// segments of a row; a second small kernel then merges the segments' (best
+// score, index, sum) records.  Noise depends on (row, index) only, so the split
+// changes nothing in the draw.  The pass is bound by the vector ALU (ten Philox
+// rounds per four logits plus three transcendentals per logit), not by HBM: a
+// decode step reads only batch x vocab logits.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <climits>
 
 #include "common.h"
@@ -121,16 +126,28 @@ __device__ __forceinline__ void better(float &z, int &i, float oz, int oi)
     }
 }
 
+// What a segment of a row leaves for the merge.
+struct SegmentRecord {
+    float best_z;
+    int32_t best_i;
+    float ref2;  // reference exponent of `s`, log2 units
+    float s;
+};
+
+// Workgroup (x, y) takes segment y of gridDim.y of row x.  With one segment it
+// writes the row's results; with more it writes its record to `records`
+// [row][segment].
 template <int DT, bool VEC, bool NOISE, int kThreads>
 __global__ __launch_bounds__(kThreads) void sample_tokens_kernel(
     const void *__restrict__ logits, int32_t *__restrict__ tokens_out, float *__restrict__ logp_out,
-    int vocab, int64_t stride, float inv_t, uint2 key, uint2 off)
+    SegmentRecord *__restrict__ records, int vocab, int64_t stride, float inv_t, uint2 key, uint2 off)
 {
     constexpr int kWaves = kThreads / 64;
     __shared__ float s_f[kWaves];
     __shared__ int s_i[kWaves];
     const int64_t row64 = blockIdx.x;
     const uint32_t row = (uint32_t)row64;
+    const int seg = blockIdx.y, n_seg = gridDim.y;
     const int tid = threadIdx.x;
     constexpr int EB = (DT == RLHF_F32) ? 4 : 2;
     const char *base = (const char *)logits + row64 * stride * EB;
@@ -140,7 +157,8 @@ __global__ __launch_bounds__(kThreads) void sample_tokens_kernel(
         constexpr int E = (DT == RLHF_F32) ? 4 : 8;
         const int nvec = vocab / E;
         const uint4 *p = (const uint4 *)base;
-        for (int i = tid; i < nvec; i += kThreads) {
+        const int i_begin = (int)((int64_t)nvec * seg / n_seg), i_end = (int)((int64_t)nvec * (seg + 1) / n_seg);
+        for (int i = i_begin + tid; i < i_end; i += kThreads) {
             const uint4 u = load16(p + i);
             if constexpr (DT == RLHF_F32) {
                 const float y[4] = {__uint_as_float(u.x) * inv_t, __uint_as_float(u.y) * inv_t,
@@ -156,10 +174,11 @@ __global__ __launch_bounds__(kThreads) void sample_tokens_kernel(
             }
         }
         const int done = nvec * E;
-        if (tid < vocab - done)
+        if (seg == n_seg - 1 && tid < vocab - done)
             take1<NOISE>(st, load_scalar<DT>(base, done + tid) * inv_t, done + tid, row, off, key);
     } else {
-        for (int v = tid; v < vocab; v += kThreads)
+        const int v_begin = (int)((int64_t)vocab * seg / n_seg), v_end = (int)((int64_t)vocab * (seg + 1) / n_seg);
+        for (int v = v_begin + tid; v < v_end; v += kThreads)
             take1<NOISE>(st, load_scalar<DT>(base, v) * inv_t, v, row, off, key);
     }
 
@@ -179,7 +198,7 @@ __global__ __launch_bounds__(kThreads) void sample_tokens_kernel(
 #pragma unroll
     for (int k = 1; k < kWaves; ++k)
         better(z, idx, s_f[k], s_i[k]);
-    if (idx == INT_MAX)  // nothing but -inf / NaN in the row
+    if (idx == INT_MAX && n_seg == 1)  // nothing but -inf / NaN in the row
         idx = 0;
     __syncthreads();
 
@@ -202,25 +221,75 @@ __global__ __launch_bounds__(kThreads) void sample_tokens_kernel(
 #pragma unroll
         for (int k = 1; k < kWaves; ++k)
             s += s_f[k];
-        tokens_out[row64] = idx;
-        if (logp_out)
-            logp_out[row64] = load_scalar<DT>(base, idx) * inv_t - (ref2 + log2f(s)) * kLn2;
+        if (n_seg > 1) {
+            records[row64 * n_seg + seg] = SegmentRecord{z, idx, ref2, s};
+        } else {
+            tokens_out[row64] = idx;
+            if (logp_out)
+                logp_out[row64] = load_scalar<DT>(base, idx) * inv_t - (ref2 + log2f(s)) * kLn2;
+        }
     }
+}
+
+// One lane per row: the best of the segments' candidates (ties to the lower
+// index) and the sum of their exponentials.
+template <int DT>
+__global__ __launch_bounds__(256) void sample_merge_kernel(
+    const void *__restrict__ logits, const SegmentRecord *__restrict__ records, int32_t *__restrict__ tokens_out,
+    float *__restrict__ logp_out, int64_t n_rows, int n_seg, int64_t stride, float inv_t)
+{
+    const int64_t row = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (row >= n_rows)
+        return;
+    const SegmentRecord *rec = records + row * n_seg;
+    float z = -INFINITY, ref2 = kNoRef * kLog2e;
+    int idx = INT_MAX;
+    for (int k = 0; k < n_seg; ++k) {
+        better(z, idx, rec[k].best_z, rec[k].best_i);
+        ref2 = fmaxf(ref2, rec[k].ref2);
+    }
+    float s = 0.f;
+    for (int k = 0; k < n_seg; ++k)
+        s += rec[k].s * fast_exp2(rec[k].ref2 - ref2);
+    if (idx == INT_MAX)  // nothing but -inf / NaN in the row
+        idx = 0;
+    tokens_out[row] = idx;
+    if (logp_out) {
+        constexpr int EB = (DT == RLHF_F32) ? 4 : 2;
+        const char *base = (const char *)logits + row * stride * EB;
+        logp_out[row] = load_scalar<DT>(base, idx) * inv_t - (ref2 + log2f(s)) * kLn2;
+    }
+}
+
+// Segments per row: enough workgroups of 1024 lanes for two per compute unit,
+// at most kMaxSegments, none shorter than 8192 entries; 1 without a workspace.
+constexpr int kMaxSegments = 8;
+constexpr int kTargetGroups = 512;
+
+int segments(int64_t n_rows, int vocab, bool have_workspace)
+{
+    if (!have_workspace || n_rows >= kTargetGroups)
+        return 1;
+    const int64_t want = (kTargetGroups + n_rows - 1) / n_rows;
+    const int64_t fit = std::max<int64_t>(vocab / 8192, 1);
+    return (int)std::min<int64_t>(std::min<int64_t>(want, fit), kMaxSegments);
 }
 
 template <int DT>
 int launch(const void *logits, int32_t *tokens, float *logp, int64_t n, int vocab, int64_t stride, bool vec,
-           float temperature, uint64_t seed, uint64_t offset, hipStream_t s)
+           float temperature, uint64_t seed, uint64_t offset, void *workspace, hipStream_t s)
 {
-    const dim3 grid((unsigned)n);
+    const int n_seg = segments(n, vocab, workspace != nullptr);
+    SegmentRecord *records = (SegmentRecord *)workspace;
+    const dim3 grid((unsigned)n, (unsigned)n_seg);
     const uint2 key = make_uint2((uint32_t)seed, (uint32_t)(seed >> 32));
     const uint2 off = make_uint2((uint32_t)offset, (uint32_t)(offset >> 32));
     const bool noise = temperature > 0.f;
     const bool wide = n < kFewRows;
     const float inv_t = noise ? 1.0f / temperature : 1.0f;
 #define RLHF_SAMPLE_LAUNCH(V, N, T)                                                                       \
-    hipLaunchKernelGGL((sample_tokens_kernel<DT, V, N, T>), grid, dim3(T), 0, s, logits, tokens, logp, vocab, \
-                       stride, inv_t, key, off)
+    hipLaunchKernelGGL((sample_tokens_kernel<DT, V, N, T>), grid, dim3(T), 0, s, logits, tokens, logp, records, \
+                       vocab, stride, inv_t, key, off)
 #define RLHF_SAMPLE_PICK(V, N)          \
     do {                                \
         if (wide)                       \
@@ -239,15 +308,21 @@ int launch(const void *logits, int32_t *tokens, float *logp, int64_t n, int voca
 #undef RLHF_SAMPLE_PICK
 #undef RLHF_SAMPLE_LAUNCH
     RLHF_LAUNCH_CHECK("sample_tokens_kernel");
+    if (n_seg > 1) {
+        hipLaunchKernelGGL((sample_merge_kernel<DT>), dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, logits,
+                           records, tokens, logp, n, n_seg, stride, inv_t);
+        RLHF_LAUNCH_CHECK("sample_merge_kernel");
+    }
     return RLHF_OK;
 }
 
 }  // namespace
 }  // namespace rlhf
 
-extern "C" int rlhf_sample_tokens(const void *logits, int32_t *tokens_out, float *logp_out, int64_t n_rows,
-                                  int32_t vocab, int64_t row_stride_elems, int32_t logits_dtype,
-                                  float temperature, uint64_t seed, uint64_t offset, void *stream)
+static int sample_tokens_impl(const void *logits, int32_t *tokens_out, float *logp_out, int64_t n_rows,
+                              int32_t vocab, int64_t row_stride_elems, int32_t logits_dtype, float temperature,
+                              uint64_t seed, uint64_t offset, void *workspace, size_t workspace_bytes,
+                              void *stream)
 {
     using namespace rlhf;
     if (n_rows < 0 || vocab <= 0 || !(temperature >= 0.f))
@@ -268,17 +343,55 @@ extern "C" int rlhf_sample_tokens(const void *logits, int32_t *tokens_out, float
     const int eb = elem_bytes(logits_dtype);
     if ((uintptr_t)logits % eb)
         return fail(RLHF_ERR_INVALID, "logits not aligned to their element size");
+    if (workspace) {
+        const size_t need = (size_t)n_rows * segments(n_rows, vocab, true) * sizeof(SegmentRecord);
+        if ((uintptr_t)workspace % 16)
+            return fail(RLHF_ERR_INVALID, "workspace must be 16-byte aligned");
+        if (workspace_bytes < need)
+            return fail(RLHF_ERR_INVALID, "workspace holds %zu bytes, %zu needed", workspace_bytes, need);
+    }
     const bool vec = ((uintptr_t)logits % 16 == 0) && ((row_stride_elems * eb) % 16 == 0);
     hipStream_t s = (hipStream_t)stream;
     switch (logits_dtype) {
     case RLHF_F16:
         return launch<RLHF_F16>(logits, tokens_out, logp_out, n_rows, vocab, row_stride_elems, vec, temperature,
-                                seed, offset, s);
+                                seed, offset, workspace, s);
     case RLHF_BF16:
         return launch<RLHF_BF16>(logits, tokens_out, logp_out, n_rows, vocab, row_stride_elems, vec,
-                                 temperature, seed, offset, s);
+                                 temperature, seed, offset, workspace, s);
     default:
         return launch<RLHF_F32>(logits, tokens_out, logp_out, n_rows, vocab, row_stride_elems, vec, temperature,
-                                seed, offset, s);
+                                seed, offset, workspace, s);
     }
+}
+
+extern "C" int rlhf_sample_tokens(const void *logits, int32_t *tokens_out, float *logp_out, int64_t n_rows,
+                                  int32_t vocab, int64_t row_stride_elems, int32_t logits_dtype,
+                                  float temperature, uint64_t seed, uint64_t offset, void *stream)
+{
+    return sample_tokens_impl(logits, tokens_out, logp_out, n_rows, vocab, row_stride_elems, logits_dtype,
+                              temperature, seed, offset, nullptr, 0, stream);
+}
+
+extern "C" int rlhf_sample_tokens_workspace_bytes(int64_t n_rows, int32_t vocab, size_t *out_bytes)
+{
+    using namespace rlhf;
+    if (!out_bytes)
+        return fail(RLHF_ERR_INVALID, "NULL out_bytes");
+    if (n_rows < 0 || vocab <= 0)
+        return fail(RLHF_ERR_INVALID, "n_rows=%lld vocab=%d", (long long)n_rows, vocab);
+    // at least one record, so that a caller can always allocate what is asked for
+    *out_bytes = (size_t)std::max<int64_t>(n_rows, 1) * segments(n_rows, vocab, true) * sizeof(SegmentRecord);
+    return RLHF_OK;
+}
+
+extern "C" int rlhf_sample_tokens_split(const void *logits, int32_t *tokens_out, float *logp_out, int64_t n_rows,
+                                        int32_t vocab, int64_t row_stride_elems, int32_t logits_dtype,
+                                        float temperature, uint64_t seed, uint64_t offset, void *workspace,
+                                        size_t workspace_bytes, void *stream)
+{
+    if (!workspace)
+        return rlhf::fail(RLHF_ERR_INVALID, "NULL workspace");
+    return sample_tokens_impl(logits, tokens_out, logp_out, n_rows, vocab, row_stride_elems, logits_dtype,
+                              temperature, seed, offset, workspace, workspace_bytes, stream);
 }

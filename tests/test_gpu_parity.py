@@ -1,5 +1,5 @@
 """GPU parity: the HIP library, called through its C ABI, against the fp64 CPU
-oracle on the same seeded inputs.  Tolerances are the ones the task fixes:
+oracle on the same seeded inputs.  Tolerances are fixed in advance:
 2e-3 max-abs on attention outputs, 1e-3 on log-probs and KL (fp32
 accumulation), bit-exact for every integer / byte result."""
 import numpy as np
@@ -403,7 +403,7 @@ def test_reward_shaping_matches_oracle(gu, oracle, cfg_index, n, penalty):
 
 
 # ---------------------------------------------------------------- sampling ----
-def _check_sampling(gu, oracle, logits, temperature, seed, offset, vocab=None, stride=0):
+def _check_sampling(gu, oracle, logits, temperature, seed, offset, vocab=None, stride=0, split=False):
     """The sampled decision is an argmax of fp32 scores on the GPU and of fp64
     scores in the oracle, so a near-tie may legitimately resolve differently: the
     GPU's token must reach the oracle's maximum perturbed score within 1e-3, and
@@ -411,7 +411,17 @@ def _check_sampling(gu, oracle, logits, temperature, seed, offset, vocab=None, s
     n = logits.shape[0]
     tok = torch.full((n,), -7, dtype=torch.int32, device=gu.DEV)
     logp = torch.full((n,), float("nan"), dtype=torch.float32, device=gu.DEV)
-    if vocab is None:
+    if split:   # rows cut into segments; scratch poisoned so that a stale record shows
+        v_eff = logits.shape[1] if vocab is None else vocab
+        ws = torch.full((rb.rlhf_sample_tokens_workspace_bytes(n, v_eff),), 0xFF, dtype=torch.uint8,
+                        device=gu.DEV)
+        if vocab is None:
+            rb.rlhf_sample_tokens_split(logits, tok, temperature, seed, ws, offset, logp_out=logp)
+        else:
+            rb.rlhf_sample_tokens_split(logits, tok, temperature, seed, ws, offset, logp_out=logp, n_rows=n,
+                                        vocab=vocab, row_stride_elems=stride,
+                                        logits_dtype=rb.dtype_code(logits.dtype))
+    elif vocab is None:
         rb.rlhf_sample_tokens(logits, tok, temperature, seed, offset, logp_out=logp)
     else:
         rb.rlhf_sample_tokens(logits, tok, temperature, seed, offset, logp_out=logp, n_rows=n, vocab=vocab,
@@ -449,6 +459,46 @@ def test_sampling_matches_oracle(gu, oracle, cfg_index, n, temperature):
     if temperature > 0:
         got2, _, _ = _check_sampling(gu, oracle, actor, temperature, 0xC0FFEE1234, 18)
         assert (got != got2).mean() > 0.5                     # a new offset gives a new draw
+
+
+@pytest.mark.parametrize("cfg_index,n", [(1, 4), (2, 16), (5, 128), (3, 300), (3, 600)])   # 600 rows: no split left
+@pytest.mark.parametrize("temperature", [1.0, 0.0])
+def test_sampling_split_rows_matches_oracle_and_the_unsplit_draw(gu, oracle, cfg_index, n, temperature):
+    """Rows cut into segments (a decode step's few rows): same bar against the
+    oracle, and token for token the draw of the unsplit call."""
+    cfg = wl.config(cfg_index)
+    actor, _ = wl.logits(cfg, n_positions=n, device=gu.DEV)
+    got, agree, _ = _check_sampling(gu, oracle, actor, temperature, 0xC0FFEE1234, 17, split=True)
+    assert agree >= 0.98
+    tok = torch.empty(n, dtype=torch.int32, device=gu.DEV)
+    logp = torch.empty(n, dtype=torch.float32, device=gu.DEV)
+    rb.rlhf_sample_tokens(actor, tok, temperature, 0xC0FFEE1234, 17, logp_out=logp)
+    torch.cuda.synchronize()
+    assert (tok.cpu().numpy() == got).all()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("vocab,stride,offset_elems", [(70001, 70001, 0), (16384, 16392, 0), (65543, 65544, 1),
+                                                        (5, 8, 0)])
+def test_sampling_split_rows_ragged_vocab_strides_and_alignment(gu, oracle, dtype, vocab, stride, offset_elems):
+    tdt = wl.torch_dtype(dtype)
+    n = 3
+    g = torch.Generator(device=gu.DEV)
+    g.manual_seed(vocab * 17 + stride)
+    buf = (torch.randn(n * stride + 8, generator=g, device=gu.DEV) * 3).to(tdt)
+    logits = buf[offset_elems:offset_elems + n * stride].view(n, stride)
+    for T in (0.0, 1.3):
+        _check_sampling(gu, oracle, logits, T, 5, 2 ** 33 + 9, vocab=vocab, stride=stride, split=True)
+
+
+def test_sampling_split_rejects_a_short_workspace(gu):
+    logits = torch.zeros(4, 65536, dtype=torch.bfloat16, device=gu.DEV)
+    tok = torch.empty(4, dtype=torch.int32, device=gu.DEV)
+    need = rb.rlhf_sample_tokens_workspace_bytes(4, 65536)
+    assert need == 4 * 8 * 16
+    ws = torch.empty(need - 16, dtype=torch.uint8, device=gu.DEV)
+    with pytest.raises(rb.RlhfError):
+        rb.rlhf_sample_tokens_split(logits, tok, 1.0, 1, ws)
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
