@@ -69,7 +69,8 @@ def run_attention(cfg, arena: FilledArena, q, out_dtype=None, max_seq_len=0, sca
     code = wl.DTYPE_CODE[cfg.kv_dtype]
     params = rb.attn_params(cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, arena.mpps, code,
                             out_dtype=out_dtype, max_seq_len=max_seq_len, softmax_scale=scale)
-    ws = torch.empty(rb.rlhf_decode_attention_workspace_bytes(params), dtype=torch.uint8, device=DEV)
+    # scratch poisoned (NaN in every float): a merge that reads a partial nobody wrote shows up
+    ws = torch.full((rb.rlhf_decode_attention_workspace_bytes(params),), 0xFF, dtype=torch.uint8, device=DEV)
     odt = torch.float32 if out_dtype == rb.RLHF_F32 else wl.torch_dtype(cfg.kv_dtype)
     out = torch.full((cfg.batch, cfg.n_q_heads, cfg.head_dim), float("nan"), dtype=odt, device=DEV)
     rb.rlhf_decode_attention(params, q, k, v, table, lens, out, ws)

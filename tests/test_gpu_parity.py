@@ -218,6 +218,32 @@ def test_attention_degenerate_lengths_and_scale(gu, oracle):
         A.close()
 
 
+@pytest.mark.parametrize("heads", [(2, 2), (8, 2)])
+def test_attention_many_sequences_most_of_them_empty(gu, oracle, heads):
+    """More sequences than a workgroup has lanes (several lengths per lane in the
+    page-count prefix), two thirds of them without a single cached token, runs of
+    empty ones at both ends."""
+    hq, hkv = heads
+    cfg = wl.small_variant(wl.config(2), batch=700, n_q_heads=hq, n_kv_heads=hkv, len_lo=0, len_hi=40)
+    rng = np.random.default_rng(700 + hq)
+    lens = rng.integers(1, 41, cfg.batch).astype(np.int32)
+    lens[rng.random(cfg.batch) < 0.66] = 0
+    lens[:9] = 0
+    lens[-5:] = 0
+    q, ks, vs = wl.qkv(cfg, lens, device=gu.DEV)
+    A = gu.FilledArena(cfg, lens, ks, vs)
+    try:
+        table, hl, _ = A.host_state()
+        assert hl.tolist() == lens.tolist()
+        expect = gu.oracle_attention(oracle, cfg, q, ks, vs, table, lens, A.n_pages)
+        out = gu.run_attention(cfg, A, q, out_dtype=rb.RLHF_F32).cpu().numpy().astype(np.float64)
+        assert np.isfinite(out).all()
+        assert (out[lens == 0] == 0).all()
+        assert np.abs(out - expect).max() <= ATTN_TOL
+    finally:
+        A.close()
+
+
 def test_attention_is_bit_identical_under_page_permutation(gu):
     base = wl.small_variant(wl.config(3), batch=4, n_q_heads=8, n_kv_heads=8, len_lo=100, len_hi=700)
     lens = wl.seq_lengths(base)
