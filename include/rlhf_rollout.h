@@ -320,6 +320,13 @@ int rlhf_prefill_attention(const rlhf_attn_params *params, const void *q, const 
                            int32_t max_q_len, const void *k_arena, const void *v_arena,
                            const int32_t *page_table, const int32_t *seq_lens, void *out, void *stream);
 
+/* Measurement aid, not a step of the method: reads `bytes` (rounded down to
+ * 16) of `buffer` (dev, 16-byte aligned) once with the 16-byte streaming loads
+ * the kernels above use and does nothing else, so that its duration gives the
+ * device's practical read ceiling to set beside the published HBM peak.  sink
+ * (dev uint32 or NULL) only keeps the loads alive.  Asynchronous on stream. */
+int rlhf_probe_stream_read(const void *buffer, size_t bytes, uint32_t *sink, void *stream);
+
 /* Text for the most recent failure on this thread ("" if none). */
 const char *rlhf_last_error_string(void);
 

@@ -15,7 +15,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librlhf_rollout.so")
-SOURCES = ["error.cpp", "alloc_sim.cpp", "arena.hip", "attention.hip", "logprob_kl.hip", "sampling.hip", "prefill.hip"]
+SOURCES = ["error.cpp", "alloc_sim.cpp", "arena.hip", "attention.hip", "logprob_kl.hip", "sampling.hip", "prefill.hip", "probe.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 FLAGS = [
