@@ -555,3 +555,54 @@ def test_sampling_frequencies_on_the_gpu_follow_softmax(gu):
     counts = np.bincount(tok.cpu().numpy(), minlength=8)
     chi2 = ((counts - N * p) ** 2 / (N * p)).sum()
     assert chi2 < scipy.stats.chi2.ppf(1 - 1e-6, 7), chi2
+
+
+# ------------------------------------------------- streams, measurement aid ----
+def test_calls_on_a_side_stream_give_the_same_results(gu):
+    """Every entry point takes the caller's stream: the same work issued on a
+    second stream (default priority) must give bit-identical outputs."""
+    cfg = wl.small_variant(wl.config(5), batch=4, n_q_heads=16, n_kv_heads=2, len_lo=100, len_hi=900,
+                           gen_len=8, vocab=32000)
+    lens = wl.seq_lengths(cfg)
+    q, ks, vs = wl.qkv(cfg, lens, device=gu.DEV)
+    actor, ref = wl.logits(cfg, device=gu.DEV)
+    tok = torch.from_numpy(wl.tokens(cfg)).to(gu.DEV)
+    A = gu.FilledArena(cfg, lens, ks, vs)
+    try:
+        k, v, table, dl = A.views()
+        params = rb.attn_params(cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, A.mpps,
+                                wl.DTYPE_CODE[cfg.kv_dtype])
+        nws = rb.rlhf_decode_attention_workspace_bytes(params)
+        sws = rb.rlhf_sample_tokens_workspace_bytes(cfg.batch, cfg.vocab)
+
+        def run(stream):
+            ws = torch.empty(nws, dtype=torch.uint8, device=gu.DEV)
+            out = torch.empty(cfg.batch, cfg.n_q_heads, cfg.head_dim, dtype=q.dtype, device=gu.DEV)
+            logp = torch.empty(cfg.n_positions, dtype=torch.float32, device=gu.DEV)
+            kl = torch.empty_like(logp)
+            draw = torch.empty(cfg.batch, dtype=torch.int32, device=gu.DEV)
+            sw = torch.empty(sws, dtype=torch.uint8, device=gu.DEV)
+            torch.cuda.synchronize()
+            rb.rlhf_decode_attention(params, q, k, v, table, dl, out, ws, stream=stream)
+            rb.rlhf_token_logprobs_kl(actor, ref, tok, logp, kl, stream=stream)
+            rb.rlhf_sample_tokens_split(actor[:cfg.batch], draw, 0.9, 77, sw, 3, stream=stream)
+            torch.cuda.synchronize()
+            return out, logp, kl, draw
+
+        base = run(None)
+        side = run(torch.cuda.Stream())
+        for a, b in zip(base, side):
+            assert torch.equal(a.view(torch.uint8), b.view(torch.uint8))
+    finally:
+        A.close()
+
+
+@pytest.mark.parametrize("nbytes", [0, 16, 4096 + 16, 256 * 4 * 16 * 3 + 48, 1 << 22])
+def test_read_probe_accepts_any_size(gu, nbytes):
+    buf = torch.zeros(max(nbytes, 16) + 16, dtype=torch.uint8, device=gu.DEV)
+    sink = torch.zeros(1, dtype=torch.int32, device=gu.DEV)
+    rb.rlhf_probe_stream_read(buf, nbytes, sink)
+    torch.cuda.synchronize()
+    assert int(sink.item()) == 0
+    with pytest.raises(rb.RlhfError):
+        rb.rlhf_probe_stream_read(buf.data_ptr() + 8, 64)
