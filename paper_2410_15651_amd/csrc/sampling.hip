@@ -268,7 +268,7 @@ constexpr int kTargetGroups = 512;
 
 int segments(int64_t n_rows, int vocab, bool have_workspace)
 {
-    if (!have_workspace || n_rows >= kTargetGroups)
+    if (!have_workspace || n_rows <= 0 || n_rows >= kTargetGroups)
         return 1;
     const int64_t want = (kTargetGroups + n_rows - 1) / n_rows;
     const int64_t fit = std::max<int64_t>(vocab / 8192, 1);

@@ -162,6 +162,38 @@ def test_compute_entry_points_validate_before_launching():
     assert e.value.status == rb.RLHF_ERR_INVALID
 
 
+def test_sampling_and_probe_entry_points_validate_before_launching():
+    # workspace sizes: 16 bytes per row and segment; segments = min(8, ceil(512 / rows), vocab / 8192), >= 1
+    assert rb.rlhf_sample_tokens_workspace_bytes(128, 128256) == 128 * 4 * 16
+    assert rb.rlhf_sample_tokens_workspace_bytes(4, 128256) == 4 * 8 * 16
+    assert rb.rlhf_sample_tokens_workspace_bytes(4, 50272) == 4 * 6 * 16
+    assert rb.rlhf_sample_tokens_workspace_bytes(4, 100) == 4 * 16
+    assert rb.rlhf_sample_tokens_workspace_bytes(1000, 128256) == 1000 * 16
+    assert rb.rlhf_sample_tokens_workspace_bytes(0, 128256) == 16          # never zero bytes
+    with pytest.raises(rb.RlhfError) as e:
+        rb.rlhf_sample_tokens_workspace_bytes(-1, 10)
+    assert e.value.status == rb.RLHF_ERR_INVALID
+    with pytest.raises(rb.RlhfError) as e:                                   # NULL workspace
+        rb.rlhf_sample_tokens_split(16, 16, 1.0, 1, 0, n_rows=4, vocab=10, logits_dtype=rb.RLHF_F32,
+                                    workspace_bytes=1024)
+    assert e.value.status == rb.RLHF_ERR_INVALID
+    with pytest.raises(rb.RlhfError) as e:                                   # workspace too small
+        rb.rlhf_sample_tokens_split(16, 16, 1.0, 1, 16, n_rows=4, vocab=65536, logits_dtype=rb.RLHF_BF16,
+                                    workspace_bytes=4 * 8 * 16 - 1)
+    assert e.value.status == rb.RLHF_ERR_INVALID
+    with pytest.raises(rb.RlhfError) as e:                                   # negative temperature
+        rb.rlhf_sample_tokens(16, 16, -1.0, 1, n_rows=4, vocab=10, logits_dtype=rb.RLHF_F32)
+    assert e.value.status == rb.RLHF_ERR_INVALID
+    rb.rlhf_sample_tokens_split(16, 16, 1.0, 1, 16, n_rows=0, vocab=10, logits_dtype=rb.RLHF_F32,
+                                workspace_bytes=16)                          # no rows: nothing to do
+    with pytest.raises(rb.RlhfError) as e:                                   # NULL / misaligned probe buffer
+        rb.rlhf_probe_stream_read(0, 64)
+    assert e.value.status == rb.RLHF_ERR_INVALID
+    with pytest.raises(rb.RlhfError) as e:
+        rb.rlhf_probe_stream_read(24, 64)
+    assert e.value.status == rb.RLHF_ERR_INVALID
+
+
 @settings(max_examples=120, deadline=None)
 @given(st.data())
 def test_random_traces_match_model(data):
