@@ -24,7 +24,11 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Calls that launch work enqueue it on that stream and return without
  *     synchronising, except where stated.
- *   - One arena may be used by one host thread at a time.
+ *   - One arena may be used by one host thread at a time, and the calls that
+ *     pass it a stream must be ordered with respect to each other on the
+ *     device (one stream, or streams the caller orders with events): the
+ *     arena's device mirrors and its append scratch change in that order.
+ *     A workspace serves one call at a time in the same sense.
  *   - Compute entry points fail with RLHF_ERR_DEVICE when no HIP device is
  *     usable; there is no CPU fallback.
  */
