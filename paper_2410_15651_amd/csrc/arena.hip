@@ -9,11 +9,13 @@
 // constant and a page freed by one sequence fits any other.
 //
 // Host bookkeeping lives in ArenaBook (arena_book.hpp).  This file adds the
-// device mirrors and three small kernels:
+// device mirrors and a few small kernels:
 //   arena_apply_kernel    applies one call's page-table / length changes, read
 //                         straight from a pinned command slot
 //   kv_scatter_kernel /   write new K/V rows into their pages in block layout
 //   kv_scatter_pages_kernel   (token by token / a whole page at a time)
+//   kv_append_step_kernel both of the above in one launch for the call a decode
+//                         step makes (one new token per listed sequence)
 //   kv_gather_kernel      reads rows back in plain [token][head][dim] order
 #include <hip/hip_runtime.h>
 
@@ -31,12 +33,13 @@ namespace {
 
 constexpr int kRingSlots = 4;
 constexpr int kPage = RLHF_PAGE_TOKENS;
-constexpr int kDescWords = 6;
+constexpr int kDescWords = 8;
 
 // Command slot layout (int32 words):
 //   [0] n_desc  [1] n_table  [2] n_lens  [3] unused
-//   desc [n_desc][6]  = token_offset, seq, start_len, n_new, whole pages before this entry,
-//                       edge tokens before this entry            (non-empty sequences only)
+//   desc [n_desc][8]  = token_offset, seq, start_len, n_new, whole pages before this entry,
+//                       edge tokens before this entry, physical page of the first new
+//                       token, unused                            (non-empty sequences only)
 //   table[n_table][2] = table_index, page (or -1)
 //   lens [n_lens][2]  = seq, new_len
 __global__ void arena_apply_kernel(const int32_t *__restrict__ cmd, int32_t *__restrict__ table,
@@ -117,6 +120,48 @@ __global__ __launch_bounds__(256) void kv_scatter_kernel(
     const int slot = pos % kPage;
     const int64_t block = ((int64_t)page * n_kv_heads + h) * (kPage * head_dim);
     const int64_t src = (t * n_kv_heads + h) * head_dim;
+    if (lane < head_dim / 8) {
+        const uint4 g = *(const uint4 *)(k_new + src + lane * 8);
+        *(uint4 *)(k_arena + block + k_block_offset(slot, lane * 8)) = g;
+    }
+    if (lane < head_dim / 2) {
+        const uint32_t w = *(const uint32_t *)(v_new + src + lane * 2);
+        v_arena[block + v_block_offset(slot, lane * 2, head_dim)] = (uint16_t)(w & 0xffffu);
+        v_arena[block + v_block_offset(slot, lane * 2 + 1, head_dim)] = (uint16_t)(w >> 16);
+    }
+}
+
+// A decode step's append -- exactly one new token for each listed sequence -- in
+// one launch: one wavefront per (sequence, kv head) places the row, and the
+// grid's first threads apply the call's page-table and length changes.  The
+// row's page comes with the descriptor (the host has just chosen it), so the
+// kernel does not depend on its own table update; everything is read straight
+// from the pinned command slot.
+__global__ __launch_bounds__(256) void kv_append_step_kernel(
+    const int32_t *__restrict__ cmd, int32_t *__restrict__ table, int32_t *__restrict__ lens,
+    const uint16_t *__restrict__ k_new, const uint16_t *__restrict__ v_new,
+    uint16_t *__restrict__ k_arena, uint16_t *__restrict__ v_arena, int n_desc, int n_table,
+    int n_kv_heads, int head_dim)
+{
+    const int32_t *c_desc = cmd + 4;
+    const int32_t *c_table = c_desc + kDescWords * n_desc;
+    const int64_t gtid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (gtid < n_table)
+        table[c_table[2 * gtid]] = c_table[2 * gtid + 1];
+    if (gtid < n_desc)
+        lens[c_desc[kDescWords * gtid + 1]] = c_desc[kDescWords * gtid + 2] + 1;
+
+    const int lane = threadIdx.x & 63;
+    const int64_t item = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (item >= (int64_t)n_desc * n_kv_heads)
+        return;
+    const int e = (int)(item / n_kv_heads);
+    const int h = (int)(item - (int64_t)e * n_kv_heads);
+    const int4 d0 = *(const int4 *)(c_desc + kDescWords * e);      // token_offset, seq, start_len, n_new
+    const int4 d1 = *(const int4 *)(c_desc + kDescWords * e + 4);  // .., .., page, ..
+    const int slot = d0.z % kPage;
+    const int64_t block = ((int64_t)d1.z * n_kv_heads + h) * (kPage * head_dim);
+    const int64_t src = ((int64_t)d0.x * n_kv_heads + h) * head_dim;
     if (lane < head_dim / 8) {
         const uint4 g = *(const uint4 *)(k_new + src + lane * 8);
         *(uint4 *)(k_arena + block + k_block_offset(slot, lane * 8)) = g;
@@ -440,6 +485,8 @@ extern "C" int rlhf_kv_arena_append(rlhf_kv_arena *arena, const int32_t *seq_ids
         d[3] = e.n_new;
         d[4] = (int32_t)whole_pages;
         d[5] = (int32_t)edge_tokens;
+        d[6] = arena->book->table()[(size_t)e.seq * arena->desc.max_pages_per_seq + e.start_len / kPage];
+        d[7] = 0;
         const int first_whole = (e.start_len + kPage - 1) / kPage;      // first page the entry may fill alone
         const int end_whole = (e.start_len + e.n_new) / kPage;           // one past the last it fills
         const int n_whole = std::max(0, end_whole - first_whole);
@@ -461,11 +508,24 @@ extern "C" int rlhf_kv_arena_append(rlhf_kv_arena *arena, const int32_t *seq_ids
     w[1] = (int32_t)plan.new_pages.size();
     w[2] = n_desc;
     w[3] = 0;
+    const int64_t heads = arena->desc.n_kv_heads;
+    if (whole_pages == 0 && edge_tokens == n_desc && ((int64_t)n_desc * heads + 3) / 4 <= 0x7fffffffLL) {
+        // a decode step: one token per sequence, placed and booked by one launch
+        // (a sequence gets at most one new page, so the grid covers the table changes)
+        hipLaunchKernelGGL(kv_append_step_kernel, dim3((unsigned)(((int64_t)n_desc * heads + 3) / 4)), dim3(256),
+                           0, s, slot->host, arena->d_table, arena->d_lens, (const uint16_t *)k_new,
+                           (const uint16_t *)v_new, (uint16_t *)arena->kv,
+                           (uint16_t *)(arena->kv + arena->half_bytes), n_desc, (int)plan.new_pages.size(),
+                           arena->desc.n_kv_heads, arena->desc.head_dim);
+        RLHF_LAUNCH_CHECK("kv_append_step_kernel");
+        RLHF_HIP_TRY(hipEventRecord(slot->done, s));
+        slot->in_flight = true;
+        return RLHF_OK;
+    }
     rc = submit_slot(arena, slot, std::max<int>(kDescWords * n_desc, (int)plan.new_pages.size()), s);
     if (rc != RLHF_OK)
         return rc;
 
-    const int64_t heads = arena->desc.n_kv_heads;
     if ((whole_pages * heads + 3) / 4 > 0x7fffffffLL || (edge_tokens * heads + 3) / 4 > 0x7fffffffLL)
         return fail(RLHF_ERR_INVALID, "append too large for one launch");
     if (whole_pages > 0) {
