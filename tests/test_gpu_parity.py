@@ -244,6 +244,29 @@ def test_attention_many_sequences_most_of_them_empty(gu, oracle, heads):
         A.close()
 
 
+def test_attention_at_the_largest_batch_one_call_takes(gu, oracle):
+    """8192 sequences (the page-count prefix of a call lives in LDS and is sized
+    for that many), short ragged caches, grouped heads; one more is refused."""
+    cfg = wl.small_variant(wl.config(2), batch=8192, n_q_heads=2, n_kv_heads=1, len_lo=0, len_hi=20)
+    rng = np.random.default_rng(8192)
+    lens = rng.integers(0, 21, cfg.batch).astype(np.int32)
+    q, ks, vs = wl.qkv(cfg, lens, device=gu.DEV)
+    A = gu.FilledArena(cfg, lens, ks, vs)
+    try:
+        table, hl, _ = A.host_state()
+        assert hl.tolist() == lens.tolist()
+        expect = gu.oracle_attention(oracle, cfg, q, ks, vs, table, lens, A.n_pages)
+        out = gu.run_attention(cfg, A, q, out_dtype=rb.RLHF_F32).cpu().numpy().astype(np.float64)
+        assert (out[lens == 0] == 0).all()
+        assert np.abs(out - expect).max() <= ATTN_TOL
+    finally:
+        A.close()
+    too_many = rb.attn_params(8193, 2, 1, 64, 2, rb.RLHF_BF16)
+    with pytest.raises(rb.RlhfError) as e:
+        rb.rlhf_decode_attention_workspace_bytes(too_many)
+    assert e.value.status == rb.RLHF_ERR_UNSUPPORTED
+
+
 def test_attention_is_bit_identical_under_page_permutation(gu):
     base = wl.small_variant(wl.config(3), batch=4, n_q_heads=8, n_kv_heads=8, len_lo=100, len_hi=700)
     lens = wl.seq_lengths(base)
