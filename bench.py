@@ -34,13 +34,13 @@ METRIC = "decode-attn HBM GB/s (% of MI355X peak) + logprob/KL tokens/sec, 1 GPU
 PMC_TRAFFIC = {
     "logprob_kl": {"sources": ["logprob_kl.hip", "device_ops.h"],
                    "sha256": "deef495df77db1122d46065078daa6de157d2779e3dd3efc06e8985e2b872b76",
-                   "bytes": 67249756626 + 9054552},
+                   "bytes": 67249781908 + 8912776},
     "decode_attn": {"sources": ["attention.hip", "mfma_ops.h", "device_ops.h"],
                     "sha256": "66cc014f0071b48cb1d5568592032ea89776ecf42ec40852f392684dcb23eb36",
-                    "bytes": 1604491913 + 8512872 + 8987274 + 2097152},
+                    "bytes": 1604493094 + 8512704 + 8987311 + 2097152},
     "prefill_attn": {"sources": ["prefill.hip", "mfma_ops.h", "device_ops.h"],
                      "sha256": "45d214783483c5c504855240ed9783f171748196265a28c8ea4735b3bf2ef93d",
-                     "bytes": 4045379091 + 3129955845},
+                     "bytes": 4044783155 + 3129962208},
 }
 
 
