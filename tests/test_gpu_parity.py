@@ -629,3 +629,14 @@ def test_read_probe_accepts_any_size(gu, nbytes):
     assert int(sink.item()) == 0
     with pytest.raises(rb.RlhfError):
         rb.rlhf_probe_stream_read(buf.data_ptr() + 8, 64)
+
+
+@pytest.mark.parametrize("cfg_index,batch", [(1, 4), (2, 5), (5, 3)])
+def test_rollout_demo_runs_the_whole_path(gu, cfg_index, batch):
+    """The demo script composes every entry point in the order a rollout uses
+    them and checks its own invariants (lengths, finite outputs, KL >= 0, the
+    arena empty after the reset)."""
+    from paper_2410_15651_amd import rollout_demo
+    r = rollout_demo.run(cfg_index, gen_len=3, batch=batch, verbose=False)
+    assert r["generated"] == 3 * batch and r["mean_kl"] >= 0
+    assert r["arena_allocated_bytes"] <= r["arena_reserved_bytes"]
