@@ -84,6 +84,11 @@ class OracleLib:
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
             ctypes.c_int64, ctypes.c_int, ctypes.c_int64, ctypes.c_int,
             ctypes.c_double, ctypes.c_uint64, ctypes.c_uint64]
+        lib.oracle_sample_tokens_topk.restype = ctypes.c_int
+        lib.oracle_sample_tokens_topk.argtypes = [
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_int64, ctypes.c_int, ctypes.c_int64, ctypes.c_int,
+            ctypes.c_double, ctypes.c_int, ctypes.c_uint64, ctypes.c_uint64]
         self._lib = lib
 
     def num_threads(self) -> int:
@@ -221,6 +226,28 @@ class OracleLib:
         return (tokens, logp, pert) if return_perturbed else (tokens, logp)
 
 
+    def sample_tokens_topk(self, logits, dtype, temperature, top_k, seed, offset=0, vocab=None,
+                           return_perturbed=False):
+        """logits [N,stride] -> (tokens [N] int32, logp [N] float64, threshold [N] float64,
+        count [N] int32[, perturbed [N,V] with -inf for removed entries])."""
+        logits = _storage(logits, dtype)
+        assert logits.ndim == 2
+        N, stride = logits.shape
+        V = stride if vocab is None else int(vocab)
+        tokens = np.zeros(N, dtype=np.int32)
+        logp = np.zeros(N, dtype=np.float64)
+        tau = np.zeros(N, dtype=np.float64)
+        count = np.zeros(N, dtype=np.int32)
+        pert = np.zeros((N, V), dtype=np.float64) if return_perturbed else None
+        rc = self._lib.oracle_sample_tokens_topk(
+            logits.ctypes.data, tokens.ctypes.data, logp.ctypes.data,
+            pert.ctypes.data if return_perturbed else None, tau.ctypes.data, count.ctypes.data,
+            N, V, stride, dtype, float(temperature), int(top_k), int(seed), int(offset))
+        if rc != 0:
+            raise ValueError("oracle_sample_tokens_topk rejected its arguments")
+        return (tokens, logp, tau, count, pert) if return_perturbed else (tokens, logp, tau, count)
+
+
 _default = None
 
 
@@ -257,6 +284,10 @@ def philox4x32_10(*args, **kw):
 
 def sample_tokens(*args, **kw):
     return _load().sample_tokens(*args, **kw)
+
+
+def sample_tokens_topk(*args, **kw):
+    return _load().sample_tokens_topk(*args, **kw)
 
 
 decode_attention.__doc__ = OracleLib.decode_attention.__doc__

@@ -24,6 +24,8 @@
  *                             sequence over the same paged cache
  *   oracle_sample_tokens      next-token sampling from softmax(logits / T) by
  *                             Gumbel-max over counter-based (Philox) uniforms
+ *   oracle_sample_tokens_topk the same draw restricted to the k largest logits
+ *                             of each row
  *
  * Inputs arrive in their storage precision (IEEE binary16, bfloat16 or
  * binary32) and are widened exactly to double; every sum, exponential and
@@ -37,6 +39,7 @@
 #include <math.h>
 #include <stddef.h>
 #include <stdint.h>
+#include <stdlib.h>
 #include <string.h>
 #ifdef _OPENMP
 #include <omp.h>
@@ -385,6 +388,94 @@ int oracle_sample_tokens(const void *logits, int32_t *tokens, double *logp, doub
         logp[i] = load_elem(logits, base + (size_t)best, dtype) * inv_t - (m + log(s));
     }
     return 0;
+}
+
+static int descending(const void *a, const void *b)
+{
+    const double x = *(const double *)a, y = *(const double *)b;
+    return (x < y) - (x > y);
+}
+
+/*
+ * Top-k sampling: the draw of oracle_sample_tokens restricted to the k largest
+ * logits of the row.  The paper only says that the actor generates responses
+ * (Section 2.1); this is the usual filter of generation code: with tau the
+ * k-th largest logit of the row (multiplicity counted), every entry below tau
+ * is removed, every entry equal to tau stays (so more than k entries survive
+ * when the k-th value is tied), and the token is drawn from softmax(logits / T)
+ * over the survivors with the SAME noise per vocabulary entry as the
+ * unrestricted draw:
+ *     C = { v : logits_v >= tau },  token = argmax_{v in C} ( logits_v / T + G_v )
+ * T == 0 is greedy.  logp = log of the survivors' renormalised softmax at the
+ * token.  k >= V keeps everything.  threshold_out, if not NULL, receives tau;
+ * count_out the number of survivors; perturbed_out as in oracle_sample_tokens,
+ * with -inf for removed entries.
+ */
+int oracle_sample_tokens_topk(const void *logits, int32_t *tokens, double *logp, double *perturbed_out,
+                              double *threshold_out, int32_t *count_out, int64_t N, int V, int64_t stride,
+                              int dtype, double temperature, int top_k, uint64_t seed, uint64_t offset)
+{
+    if (!logits || !tokens || !logp || N < 0 || V <= 0 || temperature < 0.0 || top_k < 1)
+        return -1;
+    if (stride == 0)
+        stride = V;
+    if (stride < V)
+        return -1;
+    const double inv_t = temperature > 0.0 ? 1.0 / temperature : 1.0;
+    const int k = top_k < V ? top_k : V;
+    int failed = 0;
+
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < N; ++i) {
+        const size_t base = (size_t)i * (size_t)stride;
+        double *sorted = (double *)malloc((size_t)V * sizeof(double));
+        if (!sorted) {
+#pragma omp atomic write
+            failed = 1;
+            continue;
+        }
+        for (int v = 0; v < V; ++v)
+            sorted[v] = load_elem(logits, base + v, dtype);
+        qsort(sorted, (size_t)V, sizeof(double), descending);
+        const double tau = sorted[k - 1];
+        free(sorted);
+
+        int best = -1, count = 0;
+        double best_z = -INFINITY, m = -INFINITY;
+        for (int v = 0; v < V; ++v) {
+            const double a = load_elem(logits, base + v, dtype);
+            const int kept = a >= tau;
+            double z = -INFINITY;
+            if (kept) {
+                const double y = a * inv_t;
+                z = y;
+                if (temperature > 0.0)
+                    z += -log(-log(sampling_uniform(i, v, seed, offset)));
+                ++count;
+                if (best < 0 || z > best_z) {
+                    best_z = z;
+                    best = v;
+                }
+                if (y > m)
+                    m = y;
+            }
+            if (perturbed_out)
+                perturbed_out[(size_t)i * V + v] = z;
+        }
+        double s = 0.0;
+        for (int v = 0; v < V; ++v) {
+            const double a = load_elem(logits, base + v, dtype);
+            if (a >= tau)
+                s += exp(a * inv_t - m);
+        }
+        tokens[i] = best;
+        logp[i] = load_elem(logits, base + (size_t)best, dtype) * inv_t - (m + log(s));
+        if (threshold_out)
+            threshold_out[i] = tau;
+        if (count_out)
+            count_out[i] = count;
+    }
+    return failed ? -2 : 0;
 }
 
 /*

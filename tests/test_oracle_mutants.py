@@ -110,6 +110,17 @@ MUTANTS = [
     ("prefill: wrong head group", "const int p = first + i;          /* last key this query may see */\n                const int hkv = hq / G;",
      "const int p = first + i;          /* last key this query may see */\n                const int hkv = hq % Hkv;", "prefill"),
     ("prefill: scale dropped", "const double w = exp(s * scale - m);", "const double w = exp(s - m);", "prefill"),
+    ("top-k: threshold one rank too low", "const double tau = sorted[k - 1];", "const double tau = sorted[k < V ? k : V - 1];",
+     "sampling"),
+    ("top-k: sorted upwards", "return (x < y) - (x > y);", "return (x > y) - (x < y);", "sampling"),
+    ("top-k: ties at the threshold dropped", "            const int kept = a >= tau;", "            const int kept = a > tau || v == 0;",
+     "sampling"),
+    ("top-k: log-prob normalised over the whole row", "            if (a >= tau)\n                s += exp(a * inv_t - m);",
+     "            s += exp(a * inv_t - m);", "sampling"),
+    ("top-k: noise of another entry", "z += -log(-log(sampling_uniform(i, v, seed, offset)));\n                ++count;",
+     "z += -log(-log(sampling_uniform(i, count, seed, offset)));\n                ++count;", "sampling"),
+    ("top-k: best score not restricted to survivors", "            double z = -INFINITY;\n            if (kept) {",
+     "            double z = -INFINITY;\n            if (kept || a >= tau - 1.0) {", "sampling"),
     ("padding: not zeroed", "            logp[i] = 0.0;\n            kl[i] = 0.0;\n            continue;",
      "            logp[i] = -1.0;\n            kl[i] = 0.0;\n            continue;", "logprob"),
 ]

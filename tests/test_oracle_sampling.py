@@ -98,3 +98,90 @@ def test_strides_and_16bit_inputs(oracle):
     x = t.double().numpy()[:, :20] / 0.8
     assert pert.shape == (6, 20) and tok.tolist() == pert.argmax(axis=1).tolist()
     np.testing.assert_allclose(logp, scipy.special.log_softmax(x, axis=1)[np.arange(6), tok], rtol=1e-12)
+
+
+# ------------------------------------------------------------------ top-k ----
+HAND_ROW = np.array([[0.0, 1.0, -1.0, 2.5, 0.3, -3.0, 2.5, 0.9]], dtype=np.float32)
+
+
+def test_topk_hand_cases(oracle):
+    n = 0
+    for line in open(os.path.join(GOLDEN, "topk_hand_cases.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        k, tau, count, token, logp = [x.strip() for x in line.split("|")]
+        t, lp, th, c = oracle.sample_tokens_topk(HAND_ROW, F32, 0.0, int(k), 1)
+        assert th[0] == float(np.float32(tau)) and c[0] == int(count) and t[0] == int(token), line
+        assert abs(lp[0] - float(logp)) < 1e-7, line      # the row is stored in binary32 (0.3, 0.9 are rounded)
+        n += 1
+    assert n == 6
+
+
+def test_topk_threshold_and_survivors_against_numpy(oracle):
+    rng = np.random.default_rng(7)
+    a = np.round(rng.standard_normal((30, 400)) * 3, 1).astype(np.float32)      # one decimal: plenty of ties
+    for k in (1, 2, 7, 50, 399, 400, 1000):
+        tok, logp, tau, count, pert = oracle.sample_tokens_topk(a, F32, 0.9, k, 11, 2, return_perturbed=True)
+        kth = np.sort(a.astype(np.float64), axis=1)[:, ::-1][:, min(k, 400) - 1]
+        assert np.array_equal(tau, kth)
+        kept = a.astype(np.float64) >= kth[:, None]
+        assert np.array_equal(count, kept.sum(axis=1)) and (count >= min(k, 400)).all()
+        assert np.array_equal(np.isfinite(pert), kept)                           # removed entries: -inf
+        assert tok.tolist() == pert.argmax(axis=1).tolist() and kept[np.arange(30), tok].all()
+        x = np.where(kept, a.astype(np.float64) / 0.9, -np.inf)
+        np.testing.assert_allclose(logp, scipy.special.log_softmax(x, axis=1)[np.arange(30), tok], rtol=1e-12)
+
+
+def test_topk_with_everything_kept_is_the_plain_draw(oracle):
+    rng = np.random.default_rng(8)
+    a = (rng.standard_normal((25, 333)) * 2).astype(np.float32)
+    for T in (0.0, 0.6, 1.5):
+        t0, l0, p0 = oracle.sample_tokens(a, F32, T, 99, 5, return_perturbed=True)
+        t1, l1, _, c1, p1 = oracle.sample_tokens_topk(a, F32, T, 333, 99, 5, return_perturbed=True)
+        assert t0.tolist() == t1.tolist() and (c1 == 333).all()
+        np.testing.assert_allclose(l1, l0, rtol=1e-12)
+        np.testing.assert_array_equal(p1, p0)
+        # and the survivors of a smaller k carry the same noise as in the plain draw
+        _, _, _, _, p2 = oracle.sample_tokens_topk(a, F32, T, 10, 99, 5, return_perturbed=True)
+        kept = np.isfinite(p2)
+        np.testing.assert_array_equal(p2[kept], p0[kept])
+
+
+def test_topk_of_one_is_the_argmax_whatever_the_noise(oracle):
+    rng = np.random.default_rng(9)
+    a = rng.permuted(np.tile(np.arange(200, dtype=np.float32) * 0.01, (40, 1)), axis=1)   # distinct values
+    for T in (0.0, 1.0, 50.0):
+        tok, logp, _, count = oracle.sample_tokens_topk(a, F32, T, 1, 3, 4)
+        assert tok.tolist() == a.argmax(axis=1).tolist() and (count == 1).all()
+        np.testing.assert_allclose(logp, 0.0, atol=1e-15)
+
+
+def test_topk_frequencies_follow_the_survivors_softmax(oracle):
+    logits = np.array([0.0, 1.0, -1.0, 2.5, 0.3, -3.0, 2.0, 0.9], dtype=np.float32)
+    N, T, k = 60000, 0.8, 4
+    tok, logp, tau, count = oracle.sample_tokens_topk(np.tile(logits, (N, 1)), F32, T, k, 1234, 6)
+    kept = logits >= np.sort(logits)[::-1][k - 1]
+    assert kept.sum() == 4 and (count == 4).all()
+    p = scipy.special.softmax(np.where(kept, logits.astype(np.float64) / T, -np.inf))
+    counts = np.bincount(tok, minlength=8)
+    assert (counts[~kept] == 0).all()
+    chi2 = ((counts[kept] - N * p[kept]) ** 2 / (N * p[kept])).sum()
+    assert chi2 < scipy.stats.chi2.ppf(1 - 1e-6, 3), chi2
+    np.testing.assert_allclose(logp, np.log(p[tok]), rtol=1e-12)
+
+
+def test_topk_strides_16bit_inputs_and_bad_k(oracle):
+    import torch
+    from paper_2410_15651_amd import workloads as wl
+    rng = np.random.default_rng(10)
+    t = torch.from_numpy(rng.standard_normal((6, 24)).astype(np.float32) * 3).to(torch.bfloat16)
+    tok, logp, tau, count, pert = oracle.sample_tokens_topk(wl.to_storage(t), 1, 0.8, 5, 4, 0, vocab=20,
+                                                            return_perturbed=True)
+    x = t.double().numpy()[:, :20]
+    kth = np.sort(x, axis=1)[:, ::-1][:, 4]
+    assert np.array_equal(tau, kth) and pert.shape == (6, 20)
+    xm = np.where(x >= kth[:, None], x / 0.8, -np.inf)
+    np.testing.assert_allclose(logp, scipy.special.log_softmax(xm, axis=1)[np.arange(6), tok], rtol=1e-12)
+    import pytest
+    with pytest.raises(ValueError):
+        oracle.sample_tokens_topk(np.zeros((2, 4), dtype=np.float32), F32, 1.0, 0, 1)
