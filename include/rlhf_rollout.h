@@ -263,9 +263,9 @@ int rlhf_token_logprobs_kl_rewards(const void *actor_logits, const void *ref_log
                                    const rlhf_reward_shaping *shaping, void *stream);
 
 /* ------------------------------------------------------------------------
- * Next-token sampling in one pass over the logits (Section 2.1: "the actor
- * generates responses"; this is the step between a decode step's logits and the
- * append of the next token).
+ * Next-token sampling in one pass over the logits (Section 2.1, experience
+ * generation by the actor: this is the step between a decode step's logits and
+ * the append of the next token).
  *     temperature > 0: tokens_out[i] = argmax_v ( logits[i,v]/T + G_iv ), with
  *         G_iv = -ln(-ln u_iv): an exact draw from softmax(logits[i,:]/T)
  *         (Gumbel-max).  u_iv = (k + 1/2) / 2^23 with k the top 23 bits of word
@@ -295,6 +295,22 @@ int rlhf_sample_tokens_split(const void *logits, int32_t *tokens_out, float *log
                              int32_t vocab, int64_t row_stride_elems, int32_t logits_dtype, float temperature,
                              uint64_t seed, uint64_t offset, void *workspace, size_t workspace_bytes,
                              void *stream);
+
+/* Top-k variant of the draw (Section 2.1, the same generation step with the
+ * usual truncation of the sampling distribution).  With tau_i the top_k-th
+ * largest logit of row i, only the entries with logits[i,v] >= tau_i take part:
+ * every entry tied with the top_k-th stays, so at least top_k entries survive.
+ * Each survivor gets the noise G_iv it would get in rlhf_sample_tokens (same
+ * seed, offset, row and index), the token is the argmax of logits/T + G over the
+ * survivors, and logp_out is the log of the softmax over the survivors only.
+ * tau is found exactly (comparisons of the stored values, no rounding), so the
+ * survivor set does not depend on the temperature.  top_k >= vocab is the plain
+ * draw; top_k = 1 leaves the row maximum and whatever ties with it; top_k < 1
+ * is RLHF_ERR_INVALID.  Rows holding NaN give unspecified tokens (in range).
+ * One workgroup per row: meant for decode steps (hundreds of rows). */
+int rlhf_sample_tokens_topk(const void *logits, int32_t *tokens_out, float *logp_out, int64_t n_rows,
+                            int32_t vocab, int64_t row_stride_elems, int32_t logits_dtype, float temperature,
+                            int32_t top_k, uint64_t seed, uint64_t offset, void *stream);
 
 /* ------------------------------------------------------------------------
  * Prefill attention (Section 2.1: generation starts from the prompts; this is

@@ -30,7 +30,7 @@ EXPORTS = [
     "rlhf_kv_arena_views", "rlhf_kv_arena_host_state", "rlhf_kv_arena_gather",
     "rlhf_decode_attention_workspace_bytes", "rlhf_decode_attention", "rlhf_token_logprobs_kl",
     "rlhf_token_logprobs_kl_rewards", "rlhf_sample_tokens", "rlhf_sample_tokens_workspace_bytes",
-    "rlhf_sample_tokens_split", "rlhf_prefill_attention", "rlhf_probe_stream_read",
+    "rlhf_sample_tokens_split", "rlhf_sample_tokens_topk", "rlhf_prefill_attention", "rlhf_probe_stream_read",
     "rlhf_last_error_string", "rlhf_version",
     "rlhf_alloc_sim_create", "rlhf_alloc_sim_destroy", "rlhf_alloc_sim_malloc", "rlhf_alloc_sim_free",
     "rlhf_alloc_sim_empty_cache", "rlhf_alloc_sim_stats",
@@ -124,6 +124,8 @@ def lib() -> ctypes.CDLL:
         L.rlhf_sample_tokens_workspace_bytes.argtypes = [i64, i32, P(sz)]
         L.rlhf_sample_tokens_split.argtypes = [vp, vp, vp, i64, i32, i64, i32, ctypes.c_float, ctypes.c_uint64,
                                                ctypes.c_uint64, vp, sz, vp]
+        L.rlhf_sample_tokens_topk.argtypes = [vp, vp, vp, i64, i32, i64, i32, ctypes.c_float, i32,
+                                              ctypes.c_uint64, ctypes.c_uint64, vp]
         L.rlhf_prefill_attention.argtypes = [P(AttnParams), vp, vp, i32, vp, vp, vp, vp, vp, vp]
         L.rlhf_probe_stream_read.argtypes = [vp, sz, vp, vp]
         u64 = ctypes.c_uint64
@@ -359,6 +361,20 @@ def rlhf_sample_tokens_split(logits, tokens_out, temperature, seed, workspace, o
     _check(lib().rlhf_sample_tokens_split(_ptr(logits), _ptr(tokens_out), _ptr(logp_out), n_rows, vocab,
                                           row_stride_elems, logits_dtype, temperature, seed, offset,
                                           _ptr(workspace), workspace_bytes, _stream(stream)))
+
+
+def rlhf_sample_tokens_topk(logits, tokens_out, temperature, top_k, seed, offset=0, logp_out=None, n_rows=None,
+                            vocab=None, row_stride_elems=0, logits_dtype=None, stream=None) -> None:
+    if n_rows is None:
+        n_rows = logits.shape[0]
+    if vocab is None:
+        vocab = logits.shape[1]
+        row_stride_elems = logits.stride(0)
+    if logits_dtype is None:
+        logits_dtype = dtype_code(logits.dtype)
+    _check(lib().rlhf_sample_tokens_topk(_ptr(logits), _ptr(tokens_out), _ptr(logp_out), n_rows, vocab,
+                                         row_stride_elems, logits_dtype, temperature, top_k, seed, offset,
+                                         _stream(stream)))
 
 
 def rlhf_probe_stream_read(buffer, nbytes=None, sink=None, stream=None) -> None:

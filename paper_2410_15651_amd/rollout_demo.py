@@ -7,11 +7,11 @@ reference score them):
     for every generated token:
             -> append this step's K/V rows      rlhf_kv_arena_append
             -> single-token decode attention    rlhf_decode_attention
-            -> draw the next token              rlhf_sample_tokens_split
+            -> draw the next token              rlhf_sample_tokens_split, or rlhf_sample_tokens_topk
     scoring of the generated positions          rlhf_token_logprobs_kl_rewards
     phase boundary                              rlhf_kv_arena_reset
 
-    python -m paper_2410_15651_amd.rollout_demo [config 1..5] [generated tokens] [batch]
+    python -m paper_2410_15651_amd.rollout_demo [config 1..5] [generated tokens] [batch] [top_k]
 
 There is no model here: queries, keys, values and logits are seeded random
 tensors of the configuration's shapes (one attention layer's worth), so the
@@ -25,7 +25,8 @@ import time
 import numpy as np
 
 
-def run(cfg_index: int = 2, gen_len: int = 32, batch: int | None = None, verbose: bool = True) -> dict:
+def run(cfg_index: int = 2, gen_len: int = 32, batch: int | None = None, verbose: bool = True,
+        top_k: int | None = None) -> dict:
     import torch
     from . import binding as rb
     from . import workloads as wl
@@ -96,8 +97,12 @@ def run(cfg_index: int = 2, gen_len: int = 32, batch: int | None = None, verbose
             timed("decode append", lambda: rb.rlhf_kv_arena_append(arena, ids, ones, k_t, v_t))
             timed("decode attention", lambda: rb.rlhf_decode_attention(params, q_t, k_arena, v_arena, d_table,
                                                                        d_lens, out, ws))
-            timed("sampling", lambda: rb.rlhf_sample_tokens_split(logits_t, drawn[t], 1.0, cfg.seed, sample_ws,
-                                                                  offset=t, logp_out=step_logp[t]))
+            if top_k:
+                timed("sampling", lambda: rb.rlhf_sample_tokens_topk(logits_t, drawn[t], 1.0, top_k, cfg.seed,
+                                                                     offset=t, logp_out=step_logp[t]))
+            else:
+                timed("sampling", lambda: rb.rlhf_sample_tokens_split(logits_t, drawn[t], 1.0, cfg.seed, sample_ws,
+                                                                      offset=t, logp_out=step_logp[t]))
         t_host = time.perf_counter() - t_host
 
         # ---- scoring of the generated positions: actor vs reference
@@ -149,4 +154,5 @@ def run(cfg_index: int = 2, gen_len: int = 32, batch: int | None = None, verbose
 
 if __name__ == "__main__":
     a = sys.argv[1:]
-    run(int(a[0]) if len(a) > 0 else 2, int(a[1]) if len(a) > 1 else 32, int(a[2]) if len(a) > 2 else None)
+    run(int(a[0]) if len(a) > 0 else 2, int(a[1]) if len(a) > 1 else 32, int(a[2]) if len(a) > 2 and int(a[2]) else None,
+        top_k=int(a[3]) if len(a) > 3 else None)

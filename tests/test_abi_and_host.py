@@ -186,6 +186,16 @@ def test_sampling_and_probe_entry_points_validate_before_launching():
     assert e.value.status == rb.RLHF_ERR_INVALID
     rb.rlhf_sample_tokens_split(16, 16, 1.0, 1, 16, n_rows=0, vocab=10, logits_dtype=rb.RLHF_F32,
                                 workspace_bytes=16)                          # no rows: nothing to do
+    for bad in (dict(top_k=0), dict(top_k=-3), dict(top_k=5, temperature=-0.5), dict(top_k=5, vocab=0),
+                dict(top_k=5, logits_dtype=9), dict(top_k=5, row_stride_elems=7), dict(top_k=5, logits=0),
+                dict(top_k=20, logits=0), dict(top_k=5, logits=18, logits_dtype=rb.RLHF_F32)):
+        kw = dict(logits=16, tokens_out=16, temperature=1.0, top_k=5, seed=1, n_rows=4, vocab=10,
+                  logits_dtype=rb.RLHF_BF16)
+        kw.update(bad)
+        with pytest.raises(rb.RlhfError) as e:
+            rb.rlhf_sample_tokens_topk(**kw)
+        assert e.value.status in (rb.RLHF_ERR_INVALID, rb.RLHF_ERR_UNSUPPORTED), bad
+    rb.rlhf_sample_tokens_topk(16, 16, 1.0, 5, 1, n_rows=0, vocab=10, logits_dtype=rb.RLHF_F32)   # no rows
     with pytest.raises(rb.RlhfError) as e:                                   # NULL / misaligned probe buffer
         rb.rlhf_probe_stream_read(0, 64)
     assert e.value.status == rb.RLHF_ERR_INVALID

@@ -564,6 +564,140 @@ def test_sampling_ragged_vocab_strides_and_alignment(gu, oracle, dtype, vocab, s
         _check_sampling(gu, oracle, logits, T, 5, 2 ** 33 + 9, vocab=vocab, stride=stride)
 
 
+def _check_topk(gu, oracle, logits, temperature, top_k, seed, offset, vocab=None, stride=0):
+    """Same bar as the plain draw, restricted to the oracle's survivors: the
+    survivor set is decided by exact comparisons on both sides, so a token
+    outside it is an error whatever the noise."""
+    import scipy.special
+    n = logits.shape[0]
+    tok = torch.full((n,), -7, dtype=torch.int32, device=gu.DEV)
+    logp = torch.full((n,), float("nan"), dtype=torch.float32, device=gu.DEV)
+    if vocab is None:
+        rb.rlhf_sample_tokens_topk(logits, tok, temperature, top_k, seed, offset, logp_out=logp)
+    else:
+        rb.rlhf_sample_tokens_topk(logits, tok, temperature, top_k, seed, offset, logp_out=logp, n_rows=n,
+                                   vocab=vocab, row_stride_elems=stride, logits_dtype=rb.dtype_code(logits.dtype))
+    torch.cuda.synchronize()
+    code = rb.dtype_code(logits.dtype)
+    et, el, tau, count, pert = oracle.sample_tokens_topk(wl.to_storage(logits), code, temperature, top_k, seed,
+                                                         offset, vocab=vocab, return_perturbed=True)
+    got = tok.cpu().numpy()
+    V = pert.shape[1]
+    assert ((got >= 0) & (got < V)).all()
+    rows = np.arange(n)
+    x = logits.double().cpu().numpy()[:, :V]
+    assert (x[rows, got] >= tau).all(), "a removed entry was drawn"
+    assert (count >= min(top_k, V)).all()
+    top = pert.max(axis=1)
+    assert (pert[rows, got] >= top - 1e-3).all()
+    second = np.partition(pert, V - 2, axis=1)[:, V - 2] if V > 1 else top - 1
+    clear = top - second > 1e-3
+    assert (got[clear] == et[clear]).all()
+    y = np.where(x >= tau[:, None], x * (1.0 / temperature if temperature > 0 else 1.0), -np.inf)
+    ref_logp = scipy.special.log_softmax(y, axis=1)[rows, got]       # over the survivors, at the GPU's token
+    assert np.abs(logp.cpu().numpy() - ref_logp).max() <= LOGP_TOL
+    agree = got == et
+    assert np.abs(logp.cpu().numpy()[agree] - el[agree]).max() <= LOGP_TOL
+    return got, float(agree.mean()), count
+
+
+@pytest.mark.parametrize("cfg_index,n", [(1, 16), (2, 64), (5, 128)])
+@pytest.mark.parametrize("top_k", [1, 2, 50, 1000, 1024, 1025, 5000, 40000])
+@pytest.mark.parametrize("temperature", [1.0, 0.7, 0.0])
+def test_topk_sampling_matches_oracle(gu, oracle, cfg_index, n, top_k, temperature):
+    """k from the argmax, through lists that fit the kernel's on-chip candidate
+    store, to k beyond it (the search then ends on the row itself)."""
+    cfg = wl.config(cfg_index)
+    actor, _ = wl.logits(cfg, n_positions=n, device=gu.DEV)
+    got, agree, count = _check_topk(gu, oracle, actor, temperature, top_k, 0xC0FFEE1234, 17)
+    _say(f"top-{top_k} cfg{cfg_index} T={temperature}: identical tokens {agree:.3f}, survivors "
+         f"{count.min()}..{count.max()}")
+    assert agree >= 0.97
+    x = actor.float().cpu().numpy()
+    if top_k == 1:                         # only the row maximum (and what ties with it) is left
+        assert (x[np.arange(n), got] == x.max(axis=1)).all()
+    if temperature == 0.0:                 # greedy: the first index of the maximum
+        assert (got == x.argmax(axis=1)).all()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
+@pytest.mark.parametrize("vocab,stride,offset_elems", [(1003, 1003, 0), (4099, 4104, 0), (5, 8, 0), (2048, 2048, 1),
+                                                        (1, 1, 0), (70001, 70001, 0), (65543, 65544, 1)])
+def test_topk_sampling_ragged_vocab_strides_and_alignment(gu, oracle, dtype, vocab, stride, offset_elems):
+    tdt = wl.torch_dtype(dtype)
+    n = 6
+    g = torch.Generator(device=gu.DEV)
+    g.manual_seed(vocab * 17 + stride)
+    buf = (torch.randn(n * stride + 8, generator=g, device=gu.DEV) * 3).to(tdt)
+    logits = buf[offset_elems:offset_elems + n * stride].view(n, stride)
+    for T, k in ((0.0, 3), (1.3, 1), (1.3, 7), (0.6, 900), (1.0, max(1, vocab - 1)), (1.0, vocab), (1.0, vocab + 5)):
+        _check_topk(gu, oracle, logits, T, k, 5, 2 ** 33 + 9, vocab=vocab, stride=stride)
+
+
+def test_topk_at_or_above_vocab_is_the_plain_draw(gu):
+    cfg = wl.config(2)
+    actor, _ = wl.logits(cfg, n_positions=32, device=gu.DEV)
+    a = torch.empty(32, dtype=torch.int32, device=gu.DEV)
+    b = torch.empty_like(a)
+    la = torch.empty(32, dtype=torch.float32, device=gu.DEV)
+    lb = torch.empty_like(la)
+    rb.rlhf_sample_tokens(actor, a, 0.9, 77, 3, logp_out=la)
+    for k in (cfg.vocab, cfg.vocab + 1, 2 ** 31 - 1):
+        rb.rlhf_sample_tokens_topk(actor, b, 0.9, k, 77, 3, logp_out=lb)
+        torch.cuda.synchronize()
+        assert torch.equal(a, b) and torch.equal(la, lb)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_topk_ties_at_the_threshold_all_survive(gu, oracle, dtype):
+    """Rows made of a few distinct values, so the k-th largest is tied many
+    times over: a handful of ties, more ties than the kernel keeps on chip, a
+    constant row, -0 against +0, and rows with -inf entries."""
+    tdt = wl.torch_dtype(dtype)
+    V = 30011
+    g = torch.Generator(device=gu.DEV)
+    g.manual_seed(99)
+    levels = torch.tensor([-2.0, -0.5, 0.0, 0.25, 1.5, 3.0], device=gu.DEV)
+    rows = []
+    rows.append(levels[torch.randint(0, 6, (V,), generator=g, device=gu.DEV)])                 # ~5000 per level
+    r = torch.randn(V, generator=g, device=gu.DEV)
+    r[torch.randperm(V, generator=g, device=gu.DEV)[:40]] = 5.0                                   # 40 tied at the top
+    rows.append(r)
+    rows.append(torch.full((V,), 0.75, device=gu.DEV))                                          # everything tied
+    z = torch.zeros(V, device=gu.DEV)
+    z[::2] = -0.0
+    z[5] = 1.0
+    rows.append(z)                                                                               # +-0 are one value
+    m = torch.randn(V, generator=g, device=gu.DEV)
+    m[torch.rand(V, generator=g, device=gu.DEV) < 0.9] = float("-inf")                           # a masked row
+    rows.append(m)
+    logits = torch.stack(rows).to(tdt).contiguous()
+    for k in (1, 2, 39, 40, 41, 1024, 1025, 3000, 6000, 20000, V - 1):
+        for T in (1.0, 0.0):
+            got, _, count = _check_topk(gu, oracle, logits, T, k, 31337, k)
+    # the all-tied row keeps every entry whatever k is
+    _, _, count = _check_topk(gu, oracle, logits, 1.0, 3, 1, 0)
+    assert count[2] == V and count[3] == V
+
+
+def test_topk_frequencies_on_the_gpu_follow_the_truncated_softmax(gu):
+    import scipy.special
+    import scipy.stats
+    base = np.array([0.0, 1.0, -1.0, 2.5, 0.3, -3.0, 0.9, -0.2])
+    logits = torch.tensor(base, dtype=torch.float32, device=gu.DEV)
+    N, T, k = 80000, 0.8, 3
+    tok = torch.empty(N, dtype=torch.int32, device=gu.DEV)
+    rb.rlhf_sample_tokens_topk(logits.repeat(N, 1).contiguous(), tok, T, k, 4242, 1)
+    torch.cuda.synchronize()
+    keep = np.argsort(-base)[:k]
+    p = np.zeros(8)
+    p[keep] = scipy.special.softmax(base[keep] / T)
+    counts = np.bincount(tok.cpu().numpy(), minlength=8)
+    assert counts[p == 0].sum() == 0
+    chi2 = ((counts[keep] - N * p[keep]) ** 2 / (N * p[keep])).sum()
+    assert chi2 < scipy.stats.chi2.ppf(1 - 1e-6, k - 1), chi2
+
+
 def test_sampling_frequencies_on_the_gpu_follow_softmax(gu):
     """Property that needs no oracle: the empirical distribution of many draws
     from one fixed row is softmax(logits / T)."""
@@ -640,3 +774,5 @@ def test_rollout_demo_runs_the_whole_path(gu, cfg_index, batch):
     r = rollout_demo.run(cfg_index, gen_len=3, batch=batch, verbose=False)
     assert r["generated"] == 3 * batch and r["mean_kl"] >= 0
     assert r["arena_allocated_bytes"] <= r["arena_reserved_bytes"]
+    r = rollout_demo.run(cfg_index, gen_len=2, batch=batch, verbose=False, top_k=20)     # the truncated draw
+    assert r["generated"] == 2 * batch and r["mean_logp"] <= 0
