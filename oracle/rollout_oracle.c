@@ -340,8 +340,8 @@ static double sampling_uniform(int64_t row, int v, uint64_t seed, uint64_t offse
 }
 
 /*
- * Sampling the next token from the actor's logits (Section 2.1: "the actor
- * generates responses").  With temperature T > 0 the token is drawn from
+ * Sampling the next token from the actor's logits (Section 2.1, experience
+ * generation by the actor).  With temperature T > 0 the token is drawn from
  * softmax(logits / T) by the Gumbel-max construction:
  *     token = argmax_v ( logits_v / T + G_v ),   G_v = -ln(-ln u_v)
  * with u_v the counter-based uniforms above; T == 0 means greedy argmax.  Ties
@@ -481,7 +481,7 @@ int oracle_sample_tokens_topk(const void *logits, int32_t *tokens, double *logp,
 /*
  * Causal attention for a block of new tokens per sequence ("prefill": the
  * prompt, or a chunk of it, entering the cache before generation starts;
- * Section 2.1, "the actor generates responses to prompts").  The keys and
+ * Section 2.1, generation by the actor starts from the prompts).  The keys and
  * values of the new tokens are already in the paged cache.  Sequence b brings
  * n_b = cu_q[b+1] - cu_q[b] query rows; they are the LAST n_b tokens of its
  * L_b = seq_lens[b] cached tokens, so query row i sits at logical position
