@@ -322,7 +322,12 @@ int rlhf_sample_tokens_topk(const void *logits, int32_t *tokens_out, float *logp
  * p = L_b - n_b + i and attends causally to keys 0 .. p:
  *     s_j = softmax_scale * <q_i[h,:], K_j>,  out_i[h,:] = sum_{j<=p} softmax(s)_j V_j
  * with kv head h / (n_q_heads / n_kv_heads).  Matrix-core products, fp32
- * accumulation, one pass with a running softmax reference.
+ * accumulation, one pass with a running softmax reference.  The softmax weights
+ * enter the second product rounded to fp16, and so does V: an output element is
+ * within 2^-12 * sum_j softmax(s)_j |V_j| of the exact one (plus fp32 rounding),
+ * and a BF16 cache must keep |V| below 65536 (larger entries turn into
+ * infinities in the result; BF16 magnitudes under 2^-14 are rounded to fp16
+ * subnormals, an absolute error under 2^-25).
  *
  *   params     shapes as for decode attention (max_seq_len: as there)
  *   q          dev [cu_q[batch]][n_q_heads][head_dim], qkv_dtype, rows packed

@@ -34,8 +34,13 @@
 //                     that 16 bytes hold exactly the 8 keys the lane's half h
 //                     contributes) x P^T (B operand: the registers S^T arrived
 //                     in, first 8 for the first page, last 8 for the second).
-// Probabilities go in as a high and a low 16-bit part, so the result keeps
-// fp32-level accuracy.  Row sums stay per lane until the end.  Steps that lie
+// The P.V product runs in fp16 whatever the cache type: weights are rounded to
+// fp16 (relative error 2^-12 each; a bf16 weight would carry 2^-9, more than the
+// result may be off by), kept as 2^kShift * exp(score - reference) so that none
+// that matters falls under fp16's normal range, and a bf16 V block is converted
+// on its way into LDS (exact for magnitudes from 2^-14 to 65504; larger ones
+// become infinity).  Row sums are taken in fp32 from the unrounded weights and
+// stay per lane until the end.  Steps that lie
 // entirely below a wavefront's first position need no mask; only the last few
 // ("edge") steps compare key and query positions and blank never-written keys.
 #include <hip/hip_runtime.h>
@@ -58,28 +63,26 @@ constexpr int kTileRows = 32;                      // query rows per wavefront
 constexpr int kRowsPerWg = kWgWaves * kTileRows;   // (position, head) rows per workgroup
 constexpr int kStepKeys = 2 * kPage;
 constexpr int kXcds = 8;
-constexpr float kLift = 8.0f;  // log2 units a score may exceed the reference before it is moved
+constexpr float kLift = 5.0f;   // log2 units a score may exceed the reference before it is moved
+constexpr float kShift = 10.0f;  // weights are kept as 2^kShift * exp(score - reference): at most 2^15 in fp16,
+                                 // and what falls under fp16's normal range is below 2^-24 of a row's largest
 
-// Packs the upper 16 bits of two words: `first` into the low half.
-__device__ __forceinline__ uint32_t pack_upper(uint32_t first, uint32_t second)
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef float float2_t __attribute__((ext_vector_type(2)));
+
+// Two fp32 -> packed fp16, round to nearest (v_cvt_pk_f16_f32), `first` in the low half.
+__device__ __forceinline__ uint32_t pack_f16(float first, float second)
 {
-    return __builtin_amdgcn_perm(second, first, 0x07060302u);
+    const float2_t v = {first, second};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, half2_t));
 }
 
-// fp32 pair -> packed high parts and packed remainders (see split_pair); the
-// bf16 form truncates, which the remainder absorbs.
-template <int DT>
-__device__ __forceinline__ void split2(float p0, float p1, uint32_t &hi, uint32_t &lo)
+// Two packed bf16 -> two packed fp16.  Exact for magnitudes in fp16's normal
+// range; smaller ones round (absolute error under 2^-25), 65536 and above
+// become infinity.
+__device__ __forceinline__ uint32_t bf16x2_to_f16x2(uint32_t w)
 {
-    if constexpr (DT == RLHF_BF16) {
-        const uint32_t u0 = __float_as_uint(p0), u1 = __float_as_uint(p1);
-        hi = pack_upper(u0, u1);
-        const float r0 = p0 - __uint_as_float(u0 & 0xffff0000u);  // exact
-        const float r1 = p1 - __uint_as_float(u1 & 0xffff0000u);
-        lo = pack_upper(__float_as_uint(r0), __float_as_uint(r1));
-    } else {
-        split_pair<DT>(p0, p1, hi, lo);
-    }
+    return pack_f16(__uint_as_float(w << 16), __uint_as_float(w & 0xffff0000u));
 }
 
 template <int DT, int ODT, int D>
@@ -187,8 +190,11 @@ __global__ __launch_bounds__(kThreads) void prefill_attn_kernel(
                 const int within = item - second * (kItems / 2);
                 const int d8 = within >> 4, slot = within & 15;
                 *reinterpret_cast<uint4 *>(&stage[buf][(d8 * 32 + 16 * second + slot) * 16]) = st.k[i];
-                *reinterpret_cast<uint4 *>(&stage[buf][2 * kBlockBytes + item * 16]) =
-                    make_uint4(st.v0[i].x, st.v0[i].y, st.v1[i].x, st.v1[i].y);
+                uint4 v = make_uint4(st.v0[i].x, st.v0[i].y, st.v1[i].x, st.v1[i].y);
+                if constexpr (DT == RLHF_BF16)  // the P.V product runs in fp16
+                    v = make_uint4(bf16x2_to_f16x2(v.x), bf16x2_to_f16x2(v.y), bf16x2_to_f16x2(v.z),
+                                   bf16x2_to_f16x2(v.w));
+                *reinterpret_cast<uint4 *>(&stage[buf][2 * kBlockBytes + item * 16]) = v;
             }
         }
     };
@@ -236,8 +242,8 @@ __global__ __launch_bounds__(kThreads) void prefill_attn_kernel(
         float top = max3(max3(max3(x[0], x[1], x[2]), max3(x[3], x[4], x[5]), max3(x[6], x[7], x[8])),
                          max3(max3(x[9], x[10], x[11]), max3(x[12], x[13], x[14]), x[15]), -INFINITY);
         top *= scale_log2;
-        if (__any(top > m_ref + kLift)) {
-            const float cm = fmaxf(top, __shfl_xor(top, 32));
+        if (__any(top > m_ref + (kLift + kShift))) {  // m_ref is the reference minus kShift
+            const float cm = fmaxf(top, __shfl_xor(top, 32)) - kShift;
             const float m_new = fmaxf(m_ref, cm);
             const float alpha = fast_exp2(m_ref - m_new);
             m_ref = m_new;
@@ -253,14 +259,11 @@ __global__ __launch_bounds__(kThreads) void prefill_attn_kernel(
         l_part += (((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]))) +
                   (((p[8] + p[9]) + (p[10] + p[11])) + ((p[12] + p[13]) + (p[14] + p[15])));
         // P^T as B operands: entries 8h..8h+7 of page a are registers 0..7, of page b 8..15
-        uint4 ph[2], pl[2];
+        uint4 ph[2];
 #pragma unroll
-        for (int e = 0; e < 2; ++e) {
-            split2<DT>(p[8 * e + 0], p[8 * e + 1], ph[e].x, pl[e].x);
-            split2<DT>(p[8 * e + 2], p[8 * e + 3], ph[e].y, pl[e].y);
-            split2<DT>(p[8 * e + 4], p[8 * e + 5], ph[e].z, pl[e].z);
-            split2<DT>(p[8 * e + 6], p[8 * e + 7], ph[e].w, pl[e].w);
-        }
+        for (int e = 0; e < 2; ++e)
+            ph[e] = make_uint4(pack_f16(p[8 * e + 0], p[8 * e + 1]), pack_f16(p[8 * e + 2], p[8 * e + 3]),
+                               pack_f16(p[8 * e + 4], p[8 * e + 5]), pack_f16(p[8 * e + 6], p[8 * e + 7]));
         // O^T[dim][row] += V^T[dim][key] * P^T[key][row], 16 keys (one page) per product
 #pragma unroll
         for (int e = 0; e < 2; ++e) {
@@ -280,8 +283,7 @@ __global__ __launch_bounds__(kThreads) void prefill_attn_kernel(
                 uint4 vop = *reinterpret_cast<const uint4 *>(sv + ((2 * e + h) * D + 32 * k + c) * 16);
                 if constexpr (kEdge)
                     vop = make_uint4(vop.x & m01, vop.y & m23, vop.z & m45, vop.w & m67);
-                o[k] = mfma_32x32<DT>(vop, ph[e], o[k]);
-                o[k] = mfma_32x32<DT>(vop, pl[e], o[k]);
+                o[k] = mfma_32x32<RLHF_F16>(vop, ph[e], o[k]);
             }
         }
     };

@@ -140,21 +140,30 @@ def test_prefill_first_row_is_its_value_row_and_skipped_sequences_stay_untouched
 
 def test_prefill_rows_equal_decode_steps(gu):
     """A prefill row at position p and a decode step over the first p+1 tokens
-    are the same computation: the two kernels must agree to rounding."""
+    are the same computation: the two kernels must agree to rounding.  The
+    prefill kernel feeds its weights to the matrix cores as fp16 (relative
+    rounding 2^-12 each), so an output element may differ by
+    2^-12 * sum_j w_j |v_j|; that sum is the decode kernel's own output on |V|,
+    and the bound below allows twice it plus fp32 accumulation noise."""
     cfg = wl.small_variant(wl.config(5), batch=2, n_q_heads=16, n_kv_heads=2, len_lo=150, len_hi=300)
     lens = wl.seq_lengths(cfg)
     cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
     _, ks, vs = wl.qkv(cfg, lens, device=gu.DEV)
     q = wl.query_rows(cfg, int(cu[-1]), device=gu.DEV)
     A = gu.FilledArena(cfg, lens, ks, vs)
+    A_abs = gu.FilledArena(cfg, lens, ks, [v.abs() for v in vs])
     try:
         out = _run(gu, cfg, A, q, cu, int(lens.max()), out_dtype=rb.RLHF_F32)
         last = torch.stack([q[cu[b + 1] - 1] for b in range(cfg.batch)]).contiguous()
         dec = gu.run_attention(cfg, A, last, out_dtype=rb.RLHF_F32)
+        weight_abs = gu.run_attention(cfg, A_abs, last, out_dtype=rb.RLHF_F32)
+        bound = 2.0 ** -11 * weight_abs + 1e-5
+        assert bound.max().item() < 0.5 * ATTN_TOL
         for b in range(cfg.batch):
-            assert (out[cu[b + 1] - 1] - dec[b]).abs().max().item() <= 1e-5
+            assert ((out[cu[b + 1] - 1] - dec[b]).abs() <= bound[b]).all()
     finally:
         A.close()
+        A_abs.close()
 
 
 def test_prefill_is_bit_identical_under_page_permutation(gu):
