@@ -34,13 +34,13 @@ METRIC = "decode-attn HBM GB/s (% of MI355X peak) + logprob/KL tokens/sec, 1 GPU
 PMC_TRAFFIC = {
     "logprob_kl": {"sources": ["logprob_kl.hip", "device_ops.h"],
                    "sha256": "deef495df77db1122d46065078daa6de157d2779e3dd3efc06e8985e2b872b76",
-                   "bytes": 67249781908 + 8912776},
+                   "bytes": 67249730369 + 8959864},
     "decode_attn": {"sources": ["attention.hip", "mfma_ops.h", "device_ops.h"],
                     "sha256": "66cc014f0071b48cb1d5568592032ea89776ecf42ec40852f392684dcb23eb36",
-                    "bytes": 1604493094 + 8512704 + 8987311 + 2097152},
+                    "bytes": 1604510762 + 8512736 + 8987303 + 2097152},
     "prefill_attn": {"sources": ["prefill.hip", "mfma_ops.h", "device_ops.h"],
-                     "sha256": "45d214783483c5c504855240ed9783f171748196265a28c8ea4735b3bf2ef93d",
-                     "bytes": 4044783155 + 3129962208},
+                     "sha256": "632b0d4948cc79b16d2000afb77ad2f900ecbfece3cd6510a92d2a629a33bbb9",
+                     "bytes": 4055911704 + 3129972757},
 }
 
 
@@ -210,12 +210,20 @@ def measure(cfg, K, W, dev):
     e1.record()
     torch.cuda.synchronize()
     sample_us = e0.elapsed_time(e1) / 20 * 1e3
+    for it in range(3):   # the same draw restricted to the 50 largest logits of each row
+        wk.rb.rlhf_sample_tokens_topk(rows, toks, 1.0, 50, cfg.seed, it)
+    e0.record()
+    for it in range(20):
+        wk.rb.rlhf_sample_tokens_topk(rows, toks, 1.0, 50, cfg.seed, 3 + it)
+    e1.record()
+    torch.cuda.synchronize()
+    topk_us = e0.elapsed_time(e1) / 20 * 1e3
     res = dict(
         wk=wk, n_sets=n_sets, t_total=t_total, b_step=b_step, b_attn=b_attn, b_logp=b_logp, lb=lb,
         ms_per_step=t_total / K * 1e3, value=b_step / (t_total / K) / 1e9,
         attn_gbps=b_attn / t_attn.mean() / 1e9, logp_gbps=b_logp / t_logp.mean() / 1e9,
         attn_us=t_attn.mean() * 1e6, logp_us=t_logp.mean() * 1e6, append_us=t_append.mean() * 1e6,
-        sample_us=sample_us, attn_cold=bool(kv_rotated > 512e6), stats=wk.rb.rlhf_kv_arena_stats(wk.sets[0]["arena"]))
+        sample_us=sample_us, topk_us=topk_us, attn_cold=bool(kv_rotated > 512e6), stats=wk.rb.rlhf_kv_arena_stats(wk.sets[0]["arena"]))
     return res
 
 
@@ -358,6 +366,7 @@ def main():
             "logprob_kl_us": round(m["logp_us"], 2), "append_us": round(m["append_us"], 2),
             "sample_tokens_us_per_decode_step": round(m["sample_us"], 2),
             "sample_tokens_Gelem_per_s": round(cfg.batch * cfg.vocab / m["sample_us"] / 1e3, 1),
+            "sample_tokens_top50_us_per_decode_step": round(m["topk_us"], 2),
             "arena_reserved_bytes": stats["reserved_bytes"], "arena_allocated_bytes": stats["allocated_bytes"],
             "arena_driver_allocations_after_create": 0,
         },
@@ -408,6 +417,7 @@ def main():
                 "logprob_kl_GBps": round(o["logp_gbps"], 1),
                 "logprob_kl_frac_of_peak": round(o["logp_gbps"] / HBM_PEAK_GBPS, 4),
                 "append_us": round(o["append_us"], 2), "sample_tokens_us": round(o["sample_us"], 2),
+                "sample_tokens_top50_us": round(o["topk_us"], 2),
                 "step_GBps": round(o["value"], 1)})
             o["wk"].close()
             del o
