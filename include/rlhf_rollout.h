@@ -324,7 +324,7 @@ int rlhf_sample_tokens_topk(const void *logits, int32_t *tokens_out, float *logp
  * with kv head h / (n_q_heads / n_kv_heads).  Matrix-core products, fp32
  * accumulation, one pass with a running softmax reference.  The softmax weights
  * enter the second product rounded to fp16, and so does V: an output element is
- * within 2^-12 * sum_j softmax(s)_j |V_j| of the exact one (plus fp32 rounding),
+ * within 2^-11 * sum_j softmax(s)_j |V_j| of the exact one (plus fp32 rounding),
  * and a BF16 cache must keep |V| below 65536 (larger entries turn into
  * infinities in the result; BF16 magnitudes under 2^-14 are rounded to fp16
  * subnormals, an absolute error under 2^-25).

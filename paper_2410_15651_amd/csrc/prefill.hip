@@ -35,7 +35,7 @@
 //                     contributes) x P^T (B operand: the registers S^T arrived
 //                     in, first 8 for the first page, last 8 for the second).
 // The P.V product runs in fp16 whatever the cache type: weights are rounded to
-// fp16 (relative error 2^-12 each; a bf16 weight would carry 2^-9, more than the
+// fp16 (relative error up to 2^-11 each; a bf16 weight would carry 2^-8, more than the
 // result may be off by), kept as 2^kShift * exp(score - reference) so that none
 // that matters falls under fp16's normal range, and a bf16 V block is converted
 // on its way into LDS (exact for magnitudes from 2^-14 to 65504; larger ones

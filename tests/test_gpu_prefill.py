@@ -142,9 +142,9 @@ def test_prefill_rows_equal_decode_steps(gu):
     """A prefill row at position p and a decode step over the first p+1 tokens
     are the same computation: the two kernels must agree to rounding.  The
     prefill kernel feeds its weights to the matrix cores as fp16 (relative
-    rounding 2^-12 each), so an output element may differ by
-    2^-12 * sum_j w_j |v_j|; that sum is the decode kernel's own output on |V|,
-    and the bound below allows twice it plus fp32 accumulation noise."""
+    rounding at most 2^-11 each), so an output element may differ by
+    2^-11 * sum_j w_j |v_j|; that sum is the decode kernel's own output on |V|,
+    and the bound below is that plus fp32 accumulation noise."""
     cfg = wl.small_variant(wl.config(5), batch=2, n_q_heads=16, n_kv_heads=2, len_lo=150, len_hi=300)
     lens = wl.seq_lengths(cfg)
     cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
