@@ -345,6 +345,19 @@ int rlhf_prefill_attention(const rlhf_attn_params *params, const void *q, const 
                            int32_t max_q_len, const void *k_arena, const void *v_arena,
                            const int32_t *page_table, const int32_t *seq_lens, void *out, void *stream);
 
+/* The same call with the workgroup size chosen by the caller.  A workgroup
+ * covers a block of (32 * wavefronts / (n_q_heads / n_kv_heads)) positions of
+ * one sequence and KV head: 12 wavefronts (three per SIMD) copy each K/V block
+ * into LDS for more rows and hide more latency, 8 give more, smaller
+ * workgroups when the call is small.  0 = the library's choice (12 once that
+ * still leaves some 4096 workgroups), which is what rlhf_prefill_attention
+ * uses; any other value is RLHF_ERR_INVALID.  Results are the same up to fp32
+ * summation order. */
+int rlhf_prefill_attention_wg(const rlhf_attn_params *params, const void *q, const int32_t *cu_q,
+                              int32_t max_q_len, const void *k_arena, const void *v_arena,
+                              const int32_t *page_table, const int32_t *seq_lens, void *out,
+                              int32_t wavefronts_per_workgroup, void *stream);
+
 /* Measurement aid, not a step of the method: reads `bytes` (rounded down to
  * 16) of `buffer` (dev, 16-byte aligned) once with the 16-byte streaming loads
  * the kernels above use and does nothing else, so that its duration gives the

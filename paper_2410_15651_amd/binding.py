@@ -30,7 +30,8 @@ EXPORTS = [
     "rlhf_kv_arena_views", "rlhf_kv_arena_host_state", "rlhf_kv_arena_gather",
     "rlhf_decode_attention_workspace_bytes", "rlhf_decode_attention", "rlhf_token_logprobs_kl",
     "rlhf_token_logprobs_kl_rewards", "rlhf_sample_tokens", "rlhf_sample_tokens_workspace_bytes",
-    "rlhf_sample_tokens_split", "rlhf_sample_tokens_topk", "rlhf_prefill_attention", "rlhf_probe_stream_read",
+    "rlhf_sample_tokens_split", "rlhf_sample_tokens_topk", "rlhf_prefill_attention",
+    "rlhf_prefill_attention_wg", "rlhf_probe_stream_read",
     "rlhf_last_error_string", "rlhf_version",
     "rlhf_alloc_sim_create", "rlhf_alloc_sim_destroy", "rlhf_alloc_sim_malloc", "rlhf_alloc_sim_free",
     "rlhf_alloc_sim_empty_cache", "rlhf_alloc_sim_stats",
@@ -127,6 +128,7 @@ def lib() -> ctypes.CDLL:
         L.rlhf_sample_tokens_topk.argtypes = [vp, vp, vp, i64, i32, i64, i32, ctypes.c_float, i32,
                                               ctypes.c_uint64, ctypes.c_uint64, vp]
         L.rlhf_prefill_attention.argtypes = [P(AttnParams), vp, vp, i32, vp, vp, vp, vp, vp, vp]
+        L.rlhf_prefill_attention_wg.argtypes = [P(AttnParams), vp, vp, i32, vp, vp, vp, vp, vp, i32, vp]
         L.rlhf_probe_stream_read.argtypes = [vp, sz, vp, vp]
         u64 = ctypes.c_uint64
         L.rlhf_alloc_sim_create.argtypes = [P(vp)]
@@ -291,6 +293,13 @@ def rlhf_prefill_attention(params: AttnParams, q, cu_q, max_q_len: int, k_arena,
     _check(lib().rlhf_prefill_attention(ctypes.byref(params), _ptr(q), _ptr(cu_q), int(max_q_len),
                                         _ptr(k_arena), _ptr(v_arena), _ptr(page_table), _ptr(seq_lens),
                                         _ptr(out), _stream(stream)))
+
+
+def rlhf_prefill_attention_wg(params: AttnParams, q, cu_q, max_q_len: int, k_arena, v_arena, page_table,
+                              seq_lens, out, wavefronts_per_workgroup: int, stream=None) -> None:
+    _check(lib().rlhf_prefill_attention_wg(ctypes.byref(params), _ptr(q), _ptr(cu_q), int(max_q_len),
+                                           _ptr(k_arena), _ptr(v_arena), _ptr(page_table), _ptr(seq_lens),
+                                           _ptr(out), int(wavefronts_per_workgroup), _stream(stream)))
 
 
 # ----------------------------------------------------------- logprob/KL ----

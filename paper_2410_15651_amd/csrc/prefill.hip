@@ -6,9 +6,12 @@
 // meets hundreds of query rows -- so both products run on the matrix cores and
 // the kernel is bound by them, not by HBM.
 //
-// Work split.  A workgroup (8 wavefronts, two per SIMD) owns one (sequence, KV
-// head) and a block of consecutive new positions; its 256 query rows are the
-// pairs (position, head of the KV head's group), flattened position-major.
+// Work split.  A workgroup (8 or 12 wavefronts: two or three per SIMD) owns one
+// (sequence, KV head) and a block of consecutive new positions; its 256 or 384
+// query rows are the pairs (position, head of the KV head's group), flattened
+// position-major.  Twelve wavefronts hide more of the LDS and barrier latency
+// and copy each K/V block for more rows; eight make more, smaller workgroups
+// for small calls.
 // Each wavefront keeps one tile of 32 rows (q and the output accumulators) in
 // registers.  The workgroup walks the keys 0 .. (its last position) in steps of
 // 32 keys = two pages; the step's K and V blocks are copied once from the arena
@@ -57,10 +60,11 @@ namespace rlhf {
 namespace {
 
 constexpr int kPage = RLHF_PAGE_TOKENS;
-constexpr int kThreads = 512;
-constexpr int kWgWaves = kThreads / 64;
+// Wavefronts per workgroup: twelve (three per SIMD, which the kernel's 168 registers just allow) when the
+// launch has workgroups enough to fill the chip several times over, else eight (smaller blocks of positions).
+constexpr int kWavesSmall = 8, kWavesLarge = 12;
 constexpr int kTileRows = 32;                      // query rows per wavefront
-constexpr int kRowsPerWg = kWgWaves * kTileRows;   // (position, head) rows per workgroup
+constexpr int kMaxGroup = kWavesSmall * kTileRows;  // query heads per KV head the smaller workgroup can hold
 constexpr int kStepKeys = 2 * kPage;
 constexpr int kXcds = 8;
 constexpr float kLift = 5.0f;   // log2 units a score may exceed the reference before it is moved
@@ -85,8 +89,8 @@ __device__ __forceinline__ uint32_t bf16x2_to_f16x2(uint32_t w)
     return pack_f16(__uint_as_float(w << 16), __uint_as_float(w & 0xffff0000u));
 }
 
-template <int DT, int ODT, int D>
-__global__ __launch_bounds__(kThreads) void prefill_attn_kernel(
+template <int DT, int ODT, int D, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void prefill_attn_kernel(
     const uint16_t *__restrict__ q, const int32_t *__restrict__ cu_q, const uint16_t *__restrict__ k_arena,
     const uint16_t *__restrict__ v_arena, const int32_t *__restrict__ page_table,
     const int32_t *__restrict__ seq_lens, void *__restrict__ out, int batch, int n_q_heads, int n_kv_heads,
@@ -97,6 +101,7 @@ __global__ __launch_bounds__(kThreads) void prefill_attn_kernel(
     constexpr int kBlockBytes = kPage * D * 2; // one K (or V) block of a page and head
     constexpr int kStageBytes = 4 * kBlockBytes;
     constexpr int kItems = kBlockBytes / 8;    // 16-byte copy items of K (two pages) = of V
+    constexpr int kThreads = WAVES * 64;
     constexpr int kCopies = (kItems + kThreads - 1) / kThreads;
     __shared__ __attribute__((aligned(16))) unsigned char stage[2][kStageBytes];
 
@@ -354,13 +359,13 @@ __global__ __launch_bounds__(kThreads) void prefill_attn_kernel(
     }
 }
 
-template <int DT, int ODT, int D>
-int launch(const rlhf_attn_params &p, const void *q, const int32_t *cu_q, int max_q_len, const void *k_arena,
-           const void *v_arena, const int32_t *page_table, const int32_t *seq_lens, void *out, hipStream_t s)
+template <int DT, int ODT, int D, int WAVES>
+int launch_waves(const rlhf_attn_params &p, const void *q, const int32_t *cu_q, int max_q_len, const void *k_arena,
+                 const void *v_arena, const int32_t *page_table, const int32_t *seq_lens, void *out, hipStream_t s)
 {
     const float scale = p.softmax_scale != 0.f ? p.softmax_scale : 1.0f / sqrtf((float)D);
     const int group = p.n_q_heads / p.n_kv_heads;
-    const int pos_per_wg = kRowsPerWg / group;
+    const int pos_per_wg = WAVES * kTileRows / group;
     const int n_blocks = (max_q_len + pos_per_wg - 1) / pos_per_wg;
     const int64_t units = (int64_t)p.batch * p.n_kv_heads;
     const int64_t grid = (units + kXcds - 1) / kXcds * kXcds * n_blocks;
@@ -368,7 +373,7 @@ int launch(const rlhf_attn_params &p, const void *q, const int32_t *cu_q, int ma
         return fail(RLHF_ERR_UNSUPPORTED, "prefill launch of %lld workgroups: split the call", (long long)grid);
     const int cap = p.max_pages_per_seq * kPage;
     const int max_len = (p.max_seq_len > 0 && p.max_seq_len < cap) ? p.max_seq_len : cap;
-    hipLaunchKernelGGL((prefill_attn_kernel<DT, ODT, D>), dim3((unsigned)grid), dim3(kThreads), 0, s,
+    hipLaunchKernelGGL((prefill_attn_kernel<DT, ODT, D, WAVES>), dim3((unsigned)grid), dim3(WAVES * 64), 0, s,
                        (const uint16_t *)q, cu_q, (const uint16_t *)k_arena, (const uint16_t *)v_arena,
                        page_table, seq_lens, out, p.batch, p.n_q_heads, p.n_kv_heads, p.max_pages_per_seq,
                        max_len, n_blocks, pos_per_wg, scale * kLog2e);
@@ -376,14 +381,31 @@ int launch(const rlhf_attn_params &p, const void *q, const int32_t *cu_q, int ma
     return RLHF_OK;
 }
 
+template <int DT, int ODT, int D>
+int launch(const rlhf_attn_params &p, const void *q, const int32_t *cu_q, int max_q_len, const void *k_arena,
+           const void *v_arena, const int32_t *page_table, const int32_t *seq_lens, void *out, int waves,
+           hipStream_t s)
+{
+    // the larger workgroup when it still leaves about sixteen workgroups per compute unit (256 of them)
+    const int group = p.n_q_heads / p.n_kv_heads;
+    const int pos_large = kWavesLarge * kTileRows / group;
+    const int64_t wgs_large = (int64_t)p.batch * p.n_kv_heads * ((max_q_len + pos_large - 1) / pos_large);
+    if (waves == kWavesLarge || (waves == 0 && wgs_large >= 4096))
+        return launch_waves<DT, ODT, D, kWavesLarge>(p, q, cu_q, max_q_len, k_arena, v_arena, page_table, seq_lens,
+                                                     out, s);
+    return launch_waves<DT, ODT, D, kWavesSmall>(p, q, cu_q, max_q_len, k_arena, v_arena, page_table, seq_lens, out,
+                                                 s);
+}
+
 template <int DT, int D>
 int launch_out(const rlhf_attn_params &p, const void *q, const int32_t *cu_q, int max_q_len,
                const void *k_arena, const void *v_arena, const int32_t *page_table, const int32_t *seq_lens,
-               void *out, hipStream_t s)
+               void *out, int waves, hipStream_t s)
 {
     if (p.out_dtype == RLHF_F32)
-        return launch<DT, RLHF_F32, D>(p, q, cu_q, max_q_len, k_arena, v_arena, page_table, seq_lens, out, s);
-    return launch<DT, DT, D>(p, q, cu_q, max_q_len, k_arena, v_arena, page_table, seq_lens, out, s);
+        return launch<DT, RLHF_F32, D>(p, q, cu_q, max_q_len, k_arena, v_arena, page_table, seq_lens, out, waves,
+                                       s);
+    return launch<DT, DT, D>(p, q, cu_q, max_q_len, k_arena, v_arena, page_table, seq_lens, out, waves, s);
 }
 
 }  // namespace
@@ -396,6 +418,18 @@ extern "C" int rlhf_prefill_attention(const rlhf_attn_params *params, const void
                                       const int32_t *page_table, const int32_t *seq_lens, void *out,
                                       void *stream)
 {
+    return rlhf_prefill_attention_wg(params, q, cu_q, max_q_len, k_arena, v_arena, page_table, seq_lens, out, 0,
+                                     stream);
+}
+
+extern "C" int rlhf_prefill_attention_wg(const rlhf_attn_params *params, const void *q, const int32_t *cu_q,
+                                         int32_t max_q_len, const void *k_arena, const void *v_arena,
+                                         const int32_t *page_table, const int32_t *seq_lens, void *out,
+                                         int32_t wavefronts_per_workgroup, void *stream)
+{
+    const int waves = wavefronts_per_workgroup;
+    if (waves != 0 && waves != kWavesSmall && waves != kWavesLarge)
+        return fail(RLHF_ERR_INVALID, "wavefronts_per_workgroup %d (0, %d or %d)", waves, kWavesSmall, kWavesLarge);
     if (!params)
         return fail(RLHF_ERR_INVALID, "NULL params");
     const rlhf_attn_params &p = *params;
@@ -412,8 +446,8 @@ extern "C" int rlhf_prefill_attention(const rlhf_attn_params *params, const void
         return fail(RLHF_ERR_UNSUPPORTED, "qkv_dtype %d (f16 or bf16)", p.qkv_dtype);
     if (p.out_dtype != p.qkv_dtype && p.out_dtype != RLHF_F32)
         return fail(RLHF_ERR_UNSUPPORTED, "out_dtype must be the qkv dtype or f32");
-    if (p.n_q_heads / p.n_kv_heads > kRowsPerWg)
-        return fail(RLHF_ERR_UNSUPPORTED, "more than %d query heads per kv head", kRowsPerWg);
+    if (p.n_q_heads / p.n_kv_heads > kMaxGroup)
+        return fail(RLHF_ERR_UNSUPPORTED, "more than %d query heads per kv head", kMaxGroup);
     if ((int64_t)p.max_pages_per_seq * kPage > 0x7fffffffLL ||
         (int64_t)p.batch * p.max_pages_per_seq > 0x7fffffffLL)
         return fail(RLHF_ERR_INVALID, "page table too large");
@@ -429,10 +463,12 @@ extern "C" int rlhf_prefill_attention(const rlhf_attn_params *params, const void
     if (p.qkv_dtype == RLHF_BF16) {
         if (p.head_dim == 128)
             return launch_out<RLHF_BF16, 128>(p, q, cu_q, max_q_len, k_arena, v_arena, page_table, seq_lens,
-                                              out, s);
-        return launch_out<RLHF_BF16, 64>(p, q, cu_q, max_q_len, k_arena, v_arena, page_table, seq_lens, out, s);
+                                              out, waves, s);
+        return launch_out<RLHF_BF16, 64>(p, q, cu_q, max_q_len, k_arena, v_arena, page_table, seq_lens, out, waves,
+                                         s);
     }
     if (p.head_dim == 128)
-        return launch_out<RLHF_F16, 128>(p, q, cu_q, max_q_len, k_arena, v_arena, page_table, seq_lens, out, s);
-    return launch_out<RLHF_F16, 64>(p, q, cu_q, max_q_len, k_arena, v_arena, page_table, seq_lens, out, s);
+        return launch_out<RLHF_F16, 128>(p, q, cu_q, max_q_len, k_arena, v_arena, page_table, seq_lens, out, waves,
+                                         s);
+    return launch_out<RLHF_F16, 64>(p, q, cu_q, max_q_len, k_arena, v_arena, page_table, seq_lens, out, waves, s);
 }

@@ -146,6 +146,12 @@ def test_compute_entry_points_validate_before_launching():
         rb.rlhf_prefill_attention(p, 0, 0, 8, 0, 0, 0, 0, 0)
     assert e.value.status == rb.RLHF_ERR_INVALID
     rb.rlhf_prefill_attention(p, 0, 0, 0, 0, 0, 0, 0, 0)         # no rows: nothing to do
+    for waves in (0, 8, 12):
+        rb.rlhf_prefill_attention_wg(p, 0, 0, 0, 0, 0, 0, 0, 0, waves)
+    for waves in (-1, 4, 10, 16):                                  # only 0 (auto), 8 and 12 exist
+        with pytest.raises(rb.RlhfError) as e:
+            rb.rlhf_prefill_attention_wg(p, 16, 16, 8, 16, 16, 16, 16, 16, waves)
+        assert e.value.status == rb.RLHF_ERR_INVALID
     with pytest.raises(rb.RlhfError) as e:
         rb.rlhf_prefill_attention(rb.attn_params(2, 4, 3, 64, 4, rb.RLHF_BF16), 16, 16, 8, 16, 16, 16, 16, 16)
     assert e.value.status == rb.RLHF_ERR_INVALID

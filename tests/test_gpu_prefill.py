@@ -26,6 +26,19 @@ def _say(msg):
     print(msg, flush=True)
 
 
+_WAVES = 0
+
+
+@pytest.fixture(autouse=True, params=[0, 8, 12], ids=["auto", "wg8", "wg12"])
+def _workgroup_size(request):
+    """Every test of this file runs with the library's own choice of workgroup
+    size and with each of the two sizes forced (rlhf_prefill_attention_wg)."""
+    global _WAVES
+    _WAVES = request.param
+    yield
+    _WAVES = 0
+
+
 def _run(gu, cfg, A, q, cu, max_q_len, out_dtype=None, scale=0.0, max_seq_len=0):
     k, v, table, lens = A.views()
     params = rb.attn_params(cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, A.mpps,
@@ -34,7 +47,10 @@ def _run(gu, cfg, A, q, cu, max_q_len, out_dtype=None, scale=0.0, max_seq_len=0)
     odt = torch.float32 if out_dtype == rb.RLHF_F32 else wl.torch_dtype(cfg.kv_dtype)
     out = torch.full(tuple(q.shape), float("nan"), dtype=odt, device=gu.DEV)
     cu_d = torch.from_numpy(cu).to(gu.DEV)
-    rb.rlhf_prefill_attention(params, q, cu_d, max_q_len, k, v, table, lens, out)
+    if _WAVES:
+        rb.rlhf_prefill_attention_wg(params, q, cu_d, max_q_len, k, v, table, lens, out, _WAVES)
+    else:
+        rb.rlhf_prefill_attention(params, q, cu_d, max_q_len, k, v, table, lens, out)
     torch.cuda.synchronize()
     return out
 
