@@ -34,13 +34,13 @@ METRIC = "decode-attn HBM GB/s (% of MI355X peak) + logprob/KL tokens/sec, 1 GPU
 PMC_TRAFFIC = {
     "logprob_kl": {"sources": ["logprob_kl.hip", "device_ops.h"],
                    "sha256": "deef495df77db1122d46065078daa6de157d2779e3dd3efc06e8985e2b872b76",
-                   "bytes": 67249730369 + 8959864},
+                   "bytes": 67249695440 + 9243024},
     "decode_attn": {"sources": ["attention.hip", "mfma_ops.h", "device_ops.h"],
                     "sha256": "66cc014f0071b48cb1d5568592032ea89776ecf42ec40852f392684dcb23eb36",
-                    "bytes": 1604510762 + 8512736 + 8987303 + 2097152},
+                    "bytes": 1604497325 + 8513424 + 8987268 + 2097152},
     "prefill_attn": {"sources": ["prefill.hip", "mfma_ops.h", "device_ops.h"],
-                     "sha256": "632b0d4948cc79b16d2000afb77ad2f900ecbfece3cd6510a92d2a629a33bbb9",
-                     "bytes": 4055911704 + 3129972757},
+                     "sha256": "a04d766941b9afcd95012d0b33ef9c6159fea53a4b2408f419ff7626d38e3f7e",
+                     "bytes": 4084290936 + 3322374512},
 }
 
 
