@@ -680,6 +680,41 @@ def test_topk_ties_at_the_threshold_all_survive(gu, oracle, dtype):
     assert count[2] == V and count[3] == V
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
+def test_draws_on_rows_of_nan_and_infinities_end_and_stay_in_range(gu, dtype):
+    """Rows a draw has no defined answer for (all NaN, all +inf, all -inf, a few
+    numbers among NaN): every kernel loop has a bound that does not depend on the
+    data, so the calls return, and the tokens they leave are valid indices.
+    Rows next to them keep their normal result."""
+    tdt = wl.torch_dtype(dtype)
+    V = 9001
+    g = torch.Generator(device=gu.DEV)
+    g.manual_seed(5)
+    good = (torch.randn(V, generator=g, device=gu.DEV) * 2).to(tdt)
+    few = torch.full((V,), float("nan"), device=gu.DEV)
+    few[[3, 77, 4000]] = torch.tensor([0.5, 2.0, -1.0], device=gu.DEV)
+    rows = torch.stack([good.float(), torch.full((V,), float("nan"), device=gu.DEV),
+                        torch.full((V,), float("inf"), device=gu.DEV),
+                        torch.full((V,), float("-inf"), device=gu.DEV), few, good.float()]).to(tdt).contiguous()
+    n = rows.shape[0]
+    ref_tok = torch.empty(2, dtype=torch.int32, device=gu.DEV)
+    for k in (None, 1, 5, 1500, 5000):
+        tok = torch.full((n,), -7, dtype=torch.int32, device=gu.DEV)
+        both = torch.stack([good, good]).contiguous()
+        if k is None:
+            rb.rlhf_sample_tokens(rows, tok, 1.0, 9, 2)
+            rb.rlhf_sample_tokens(both, ref_tok, 1.0, 9, 2)
+        else:
+            rb.rlhf_sample_tokens_topk(rows, tok, 1.0, k, 9, 2)
+            rb.rlhf_sample_tokens_topk(both, ref_tok, 1.0, k, 9, 2)
+        torch.cuda.synchronize()
+        t = tok.cpu().numpy()
+        assert ((t >= 0) & (t < V)).all(), (k, t)
+        assert t[0] == ref_tok.cpu().numpy()[0]          # row 0 is row 0 of the clean call
+        if k is not None and k <= 3:
+            assert t[4] in (3, 77, 4000)                  # the numbers among the NaN
+
+
 def test_topk_frequencies_on_the_gpu_follow_the_truncated_softmax(gu):
     import scipy.special
     import scipy.stats
