@@ -29,6 +29,12 @@
  *     device (one stream, or streams the caller orders with events): the
  *     arena's device mirrors and its append scratch change in that order.
  *     A workspace serves one call at a time in the same sense.
+ *   - The compute entry points (decode and prefill attention, log-prob/KL,
+ *     the draws, the read probe) allocate nothing, issue no memset or copy and
+ *     never synchronise: they may be recorded into a HIP graph on the stream
+ *     they are given and replayed; a replay reads the buffers' contents of
+ *     that moment.  rlhf_kv_arena_append may not be recorded (its bookkeeping
+ *     runs on the host at call time).
  *   - Compute entry points fail with RLHF_ERR_DEVICE when no HIP device is
  *     usable; there is no CPU fallback.
  */

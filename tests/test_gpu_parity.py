@@ -811,3 +811,72 @@ def test_rollout_demo_runs_the_whole_path(gu, cfg_index, batch):
     assert r["arena_allocated_bytes"] <= r["arena_reserved_bytes"]
     r = rollout_demo.run(cfg_index, gen_len=2, batch=batch, verbose=False, top_k=20)     # the truncated draw
     assert r["generated"] == 2 * batch and r["mean_logp"] <= 0
+
+
+def test_compute_entry_points_replay_from_a_hip_graph(gu):
+    """The compute calls allocate nothing, clear nothing with memsets and never
+    synchronise, so a caller may record them into a HIP graph.  A step's worth of
+    them (decode attention, the plain, split and top-k draws, log-prob/KL with
+    rewards, prefill attention) is captured once and replayed several times with
+    eager work and synchronisations in between; every replay must reproduce the
+    eager results bit for bit, and must follow the inputs' current contents."""
+    cfg = wl.small_variant(wl.config(5), batch=4, n_q_heads=16, n_kv_heads=2, len_lo=90, len_hi=400, vocab=40000)
+    lens = wl.seq_lengths(cfg)
+    q, ks, vs = wl.qkv(cfg, lens, device=gu.DEV)
+    A = gu.FilledArena(cfg, lens, ks, vs)
+    try:
+        k, v, table, sl = A.views()
+        code = wl.DTYPE_CODE[cfg.kv_dtype]
+        params = rb.attn_params(cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, A.mpps, code)
+        ws = torch.empty(rb.rlhf_decode_attention_workspace_bytes(params), dtype=torch.uint8, device=gu.DEV)
+        out = torch.empty_like(q)
+        actor, ref = wl.logits(cfg, n_positions=64, device=gu.DEV)
+        tok = torch.from_numpy(wl.tokens(cfg)[:64].copy()).to(gu.DEV)
+        logp, kl, reward = (torch.empty(64, dtype=torch.float32, device=gu.DEV) for _ in range(3))
+        d_plain, d_split, d_topk = (torch.empty(64, dtype=torch.int32, device=gu.DEV) for _ in range(3))
+        sws = torch.empty(rb.rlhf_sample_tokens_workspace_bytes(64, cfg.vocab), dtype=torch.uint8, device=gu.DEV)
+        cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+        cu_d = torch.from_numpy(cu).to(gu.DEV)
+        qp = wl.query_rows(cfg, int(cu[-1]), device=gu.DEV)
+        outp = torch.empty_like(qp)
+        results = [out, logp, kl, reward, d_plain, d_split, d_topk, outp]
+
+        def step():
+            rb.rlhf_decode_attention(params, q, k, v, table, sl, out, ws)
+            rb.rlhf_sample_tokens(actor, d_plain, 0.8, 11, 3)
+            rb.rlhf_sample_tokens_split(actor, d_split, 0.8, 11, sws, 3)
+            rb.rlhf_sample_tokens_topk(actor, d_topk, 0.8, 30, 11, 3)
+            rb.rlhf_token_logprobs_kl_rewards(actor, ref, tok, logp, kl, 0.1, reward_out=reward)
+            rb.rlhf_prefill_attention(params, qp, cu_d, int(lens.max()), k, v, table, sl, outp)
+
+        def eager():
+            for r in results:
+                r.view(torch.uint8).fill_(0x5A)
+            step()
+            torch.cuda.synchronize()
+            return [r.clone() for r in results]
+
+        expect = eager()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()                                      # warm-up on the capture stream
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        q2 = (q.float() * -0.5 + 0.25).to(q.dtype)
+        for rep in range(4):
+            if rep == 2:                                # new input contents in the recorded buffers
+                q.copy_(q2)
+                expect = eager()
+            for r in results:
+                r.view(torch.uint8).fill_(0xA5)         # eager work between replays; outputs poisoned
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            for r, e in zip(results, expect):
+                assert torch.equal(r.view(torch.uint8), e.view(torch.uint8)), rep
+    finally:
+        A.close()
