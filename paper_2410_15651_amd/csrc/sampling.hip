@@ -24,6 +24,11 @@
 // changes nothing in the draw.  The pass is bound by the vector ALU (ten Philox
 // rounds per four logits plus three transcendentals per logit), not by HBM: a
 // decode step reads only batch x vocab logits.
+//
+// The top-k variant keeps the entries at or above the k-th largest logit of the
+// row (ties included) and draws among them with the same per-entry noise; it
+// finds that threshold exactly and then needs noise for the survivors only, so
+// for the usual k it is cheaper than the plain draw (sample_topk_kernel below).
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
