@@ -185,3 +185,31 @@ def test_topk_strides_16bit_inputs_and_bad_k(oracle):
     import pytest
     with pytest.raises(ValueError):
         oracle.sample_tokens_topk(np.zeros((2, 4), dtype=np.float32), F32, 1.0, 0, 1)
+
+
+def test_topk_survivor_sets_are_nested_and_the_draw_is_the_plain_one_when_it_survives(oracle):
+    """Properties that hold for any logits: the threshold falls (weakly) and the
+    survivor count grows with k and is at least k; removed entries can only
+    remove the plain draw's winner, so whenever that winner is among the
+    survivors the top-k draw is the same token (same noise, smaller contest),
+    and otherwise it differs.  Checked over random rows with many ties."""
+    rng = np.random.default_rng(2024)
+    for trial in range(30):
+        V = int(rng.integers(3, 400))
+        levels = rng.normal(0, 2, size=int(rng.integers(2, 40)))
+        x = rng.choice(levels, size=(5, V)).astype(np.float32)          # few distinct values: ties everywhere
+        T = float(rng.choice([0.5, 1.0, 2.0]))
+        plain, _, pert = oracle.sample_tokens(x, 2, T, 77, trial, return_perturbed=True)
+        prev_tau, prev_cnt = None, None
+        for k in sorted(set(int(v) for v in rng.integers(1, V + 1, size=6)) | {1, V}):
+            tok, logp, tau, cnt = oracle.sample_tokens_topk(x, 2, T, k, 77, trial)
+            assert (cnt >= k).all() and (cnt == (x >= tau[:, None]).sum(axis=1)).all()
+            kth = -np.sort(-x, axis=1)[:, k - 1]
+            assert (tau == kth).all()
+            if prev_tau is not None:
+                assert (tau <= prev_tau).all() and (cnt >= prev_cnt).all()
+            prev_tau, prev_cnt = tau, cnt
+            survives = x[np.arange(5), plain] >= tau
+            assert (tok[survives] == plain[survives]).all()
+            assert (tok[~survives] != plain[~survives]).all()
+            assert (x[np.arange(5), tok] >= tau).all() and (logp <= 1e-12).all()
