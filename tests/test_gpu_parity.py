@@ -715,6 +715,28 @@ def test_draws_on_rows_of_nan_and_infinities_end_and_stay_in_range(gu, dtype):
             assert t[4] in (3, 77, 4000)                  # the numbers among the NaN
 
 
+@pytest.mark.parametrize("cfg_index,n", [(2, 64), (5, 128)])
+def test_topk_draw_is_the_plain_draw_whenever_its_winner_survives(gu, cfg_index, n):
+    """No oracle needed: both kernels score an entry with the same noise and the
+    same fp32 arithmetic, so removing entries can only change the result by
+    removing the plain draw's winner."""
+    cfg = wl.config(cfg_index)
+    actor, _ = wl.logits(cfg, n_positions=n, device=gu.DEV)
+    plain = torch.empty(n, dtype=torch.int32, device=gu.DEV)
+    rb.rlhf_sample_tokens(actor, plain, 1.0, 4711, 9)
+    x = actor.float()
+    rows = torch.arange(n, device=gu.DEV)
+    for k in (1, 7, 50, 700, 3000, 20000):
+        tok = torch.empty(n, dtype=torch.int32, device=gu.DEV)
+        rb.rlhf_sample_tokens_topk(actor, tok, 1.0, k, 4711, 9)
+        torch.cuda.synchronize()
+        tau = torch.topk(x, k, dim=1).values[:, -1]
+        survives = x[rows, plain.long()] >= tau
+        assert torch.equal(tok[survives], plain[survives])
+        assert (tok[~survives] != plain[~survives]).all()
+        assert (x[rows, tok.long()] >= tau).all()
+
+
 def test_topk_frequencies_on_the_gpu_follow_the_truncated_softmax(gu):
     import scipy.special
     import scipy.stats
