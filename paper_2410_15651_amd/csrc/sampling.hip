@@ -80,7 +80,8 @@ struct Lane {
     float s = 0.f;                 // sum 2^(y*log2e - ref2), y = a / T
 };
 
-template <bool NOISE>
+// LSE = false leaves the running sum of exponentials out (no log-probability asked for).
+template <bool NOISE, bool LSE = true>
 __device__ __forceinline__ void take(Lane &st, float y, float g, int v)
 {
     const float z = NOISE ? y + g : y;
@@ -88,6 +89,8 @@ __device__ __forceinline__ void take(Lane &st, float y, float g, int v)
         st.best_z = z;
         st.best_i = v;
     }
+    if constexpr (!LSE)
+        return;
     if (y > st.lift) {
         const float ref2 = y * kLog2e;
         st.s *= fast_exp2(st.ref2 - ref2);
@@ -98,19 +101,19 @@ __device__ __forceinline__ void take(Lane &st, float y, float g, int v)
 }
 
 // Four consecutive entries starting at a multiple of four: one Philox block.
-template <bool NOISE>
+template <bool NOISE, bool LSE = true>
 __device__ __forceinline__ void take4(Lane &st, const float (&y)[4], int v0, uint32_t row, uint2 off, uint2 key)
 {
     uint4 r = make_uint4(0, 0, 0, 0);
     if (NOISE)
         r = philox4x32_10(make_uint4((uint32_t)(v0 >> 2), row, off.x, off.y), key);
-    take<NOISE>(st, y[0], NOISE ? gumbel(r.x) : 0.f, v0);
-    take<NOISE>(st, y[1], NOISE ? gumbel(r.y) : 0.f, v0 + 1);
-    take<NOISE>(st, y[2], NOISE ? gumbel(r.z) : 0.f, v0 + 2);
-    take<NOISE>(st, y[3], NOISE ? gumbel(r.w) : 0.f, v0 + 3);
+    take<NOISE, LSE>(st, y[0], NOISE ? gumbel(r.x) : 0.f, v0);
+    take<NOISE, LSE>(st, y[1], NOISE ? gumbel(r.y) : 0.f, v0 + 1);
+    take<NOISE, LSE>(st, y[2], NOISE ? gumbel(r.z) : 0.f, v0 + 2);
+    take<NOISE, LSE>(st, y[3], NOISE ? gumbel(r.w) : 0.f, v0 + 3);
 }
 
-template <bool NOISE>
+template <bool NOISE, bool LSE = true>
 __device__ __forceinline__ void take1(Lane &st, float y, int v, uint32_t row, uint2 off, uint2 key)
 {
     float g = 0.f;
@@ -119,7 +122,7 @@ __device__ __forceinline__ void take1(Lane &st, float y, int v, uint32_t row, ui
         const uint32_t word = (v & 3) == 0 ? r.x : (v & 3) == 1 ? r.y : (v & 3) == 2 ? r.z : r.w;
         g = gumbel(word);
     }
-    take<NOISE>(st, y, g, v);
+    take<NOISE, LSE>(st, y, g, v);
 }
 
 // Larger score wins; equal scores go to the lower index.
@@ -142,7 +145,7 @@ struct SegmentRecord {
 // Workgroup (x, y) takes segment y of gridDim.y of row x.  With one segment it
 // writes the row's results; with more it writes its record to `records`
 // [row][segment].
-template <int DT, bool VEC, bool NOISE, int kThreads>
+template <int DT, bool VEC, bool NOISE, bool LSE, int kThreads>
 __global__ __launch_bounds__(kThreads) void sample_tokens_kernel(
     const void *__restrict__ logits, int32_t *__restrict__ tokens_out, float *__restrict__ logp_out,
     SegmentRecord *__restrict__ records, int vocab, int64_t stride, float inv_t, uint2 key, uint2 off)
@@ -168,23 +171,23 @@ __global__ __launch_bounds__(kThreads) void sample_tokens_kernel(
             if constexpr (DT == RLHF_F32) {
                 const float y[4] = {__uint_as_float(u.x) * inv_t, __uint_as_float(u.y) * inv_t,
                                     __uint_as_float(u.z) * inv_t, __uint_as_float(u.w) * inv_t};
-                take4<NOISE>(st, y, i * 4, row, off, key);
+                take4<NOISE, LSE>(st, y, i * 4, row, off, key);
             } else {
                 const float y0[4] = {unpack_lo<DT>(u.x) * inv_t, unpack_hi<DT>(u.x) * inv_t,
                                      unpack_lo<DT>(u.y) * inv_t, unpack_hi<DT>(u.y) * inv_t};
                 const float y1[4] = {unpack_lo<DT>(u.z) * inv_t, unpack_hi<DT>(u.z) * inv_t,
                                      unpack_lo<DT>(u.w) * inv_t, unpack_hi<DT>(u.w) * inv_t};
-                take4<NOISE>(st, y0, i * 8, row, off, key);
-                take4<NOISE>(st, y1, i * 8 + 4, row, off, key);
+                take4<NOISE, LSE>(st, y0, i * 8, row, off, key);
+                take4<NOISE, LSE>(st, y1, i * 8 + 4, row, off, key);
             }
         }
         const int done = nvec * E;
         if (seg == n_seg - 1 && tid < vocab - done)
-            take1<NOISE>(st, load_scalar<DT>(base, done + tid) * inv_t, done + tid, row, off, key);
+            take1<NOISE, LSE>(st, load_scalar<DT>(base, done + tid) * inv_t, done + tid, row, off, key);
     } else {
         const int v_begin = (int)((int64_t)vocab * seg / n_seg), v_end = (int)((int64_t)vocab * (seg + 1) / n_seg);
         for (int v = v_begin + tid; v < v_end; v += kThreads)
-            take1<NOISE>(st, load_scalar<DT>(base, v) * inv_t, v, row, off, key);
+            take1<NOISE, LSE>(st, load_scalar<DT>(base, v) * inv_t, v, row, off, key);
     }
 
     // best (score, index) of the row: wavefront butterflies, then the four wavefronts
@@ -732,9 +735,16 @@ int launch(const void *logits, int32_t *tokens, float *logp, int64_t n, int voca
     const bool noise = temperature > 0.f;
     const bool wide = n < kFewRows;
     const float inv_t = noise ? 1.0f / temperature : 1.0f;
-#define RLHF_SAMPLE_LAUNCH(V, N, T)                                                                       \
-    hipLaunchKernelGGL((sample_tokens_kernel<DT, V, N, T>), grid, dim3(T), 0, s, logits, tokens, logp, records, \
-                       vocab, stride, inv_t, key, off)
+    const bool lse = logp != nullptr;  // the sum of exponentials is only needed for the log-probability
+#define RLHF_SAMPLE_LAUNCH(V, N, T)                                                                            \
+    do {                                                                                                       \
+        if (lse)                                                                                               \
+            hipLaunchKernelGGL((sample_tokens_kernel<DT, V, N, true, T>), grid, dim3(T), 0, s, logits, tokens, \
+                               logp, records, vocab, stride, inv_t, key, off);                                 \
+        else                                                                                                   \
+            hipLaunchKernelGGL((sample_tokens_kernel<DT, V, N, false, T>), grid, dim3(T), 0, s, logits, tokens, \
+                               logp, records, vocab, stride, inv_t, key, off);                                 \
+    } while (0)
 #define RLHF_SAMPLE_PICK(V, N)          \
     do {                                \
         if (wide)                       \

@@ -540,6 +540,28 @@ def test_sampling_split_rows_ragged_vocab_strides_and_alignment(gu, oracle, dtyp
         _check_sampling(gu, oracle, logits, T, 5, 2 ** 33 + 9, vocab=vocab, stride=stride, split=True)
 
 
+@pytest.mark.parametrize("temperature", [1.0, 0.0])
+def test_sampling_without_a_log_probability_draws_the_same_tokens(gu, temperature):
+    """With logp_out NULL the kernels leave the sum of exponentials out; the
+    draw itself must not change (plain, split and ragged scalar paths)."""
+    cfg = wl.config(2)
+    actor, _ = wl.logits(cfg, n_positions=40, device=gu.DEV)
+    ws = torch.empty(rb.rlhf_sample_tokens_workspace_bytes(40, cfg.vocab), dtype=torch.uint8, device=gu.DEV)
+    a, b, c, d = (torch.empty(40, dtype=torch.int32, device=gu.DEV) for _ in range(4))
+    lp = torch.empty(40, dtype=torch.float32, device=gu.DEV)
+    rb.rlhf_sample_tokens(actor, a, temperature, 99, 4, logp_out=lp)
+    rb.rlhf_sample_tokens(actor, b, temperature, 99, 4)
+    rb.rlhf_sample_tokens_split(actor, c, temperature, 99, ws, 4)
+    ragged = actor[:, 3:3 + 30001]                      # misaligned rows: the scalar path
+    rb.rlhf_sample_tokens(ragged, d, temperature, 99, 4, n_rows=40, vocab=30001, row_stride_elems=actor.stride(0),
+                          logits_dtype=rb.dtype_code(actor.dtype))
+    e = torch.empty_like(d)
+    rb.rlhf_sample_tokens(ragged, e, temperature, 99, 4, logp_out=lp, n_rows=40, vocab=30001,
+                          row_stride_elems=actor.stride(0), logits_dtype=rb.dtype_code(actor.dtype))
+    torch.cuda.synchronize()
+    assert torch.equal(a, b) and torch.equal(a, c) and torch.equal(d, e)
+
+
 def test_sampling_split_rejects_a_short_workspace(gu):
     logits = torch.zeros(4, 65536, dtype=torch.bfloat16, device=gu.DEV)
     tok = torch.empty(4, dtype=torch.int32, device=gu.DEV)
