@@ -51,13 +51,23 @@ __device__ __forceinline__ uint4 philox4x32_10(uint4 c, uint2 k)
     constexpr uint32_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u;
 #pragma unroll
     for (int round = 0; round < 10; ++round) {
-        const uint32_t hi0 = __umulhi(M0, c.x), lo0 = M0 * c.x;
-        const uint32_t hi1 = __umulhi(M1, c.z), lo1 = M1 * c.z;
+        // one 32x32->64 multiply-add instruction per product instead of a high and a low multiply
+        const uint64_t p0 = (uint64_t)M0 * c.x, p1 = (uint64_t)M1 * c.z;
+        const uint32_t hi0 = (uint32_t)(p0 >> 32), lo0 = (uint32_t)p0;
+        const uint32_t hi1 = (uint32_t)(p1 >> 32), lo1 = (uint32_t)p1;
         c = make_uint4(hi1 ^ c.y ^ k.x, lo1, hi0 ^ c.w ^ k.y, lo0);
         k.x += 0x9E3779B9u;
         k.y += 0xBB67AE85u;
     }
     return c;
+}
+
+// ln x for normal x > 0 on the hardware log2 (v_log_f32) alone: the library
+// form adds range fix-up code for denormals, which u >= 2^-24 and
+// e = -ln u >= 2^-24 never are.
+__device__ __forceinline__ float fast_ln(float x)
+{
+    return __builtin_amdgcn_logf(x) * kLn2;
 }
 
 // Gumbel noise from one 32-bit word.
@@ -68,8 +78,8 @@ __device__ __forceinline__ float gumbel(uint32_t word)
     // c = 1 - u (exact), because a hardware log loses relative accuracy there.
     const float c = 1.0f - u;
     const float series = c * (1.0f + c * (0.5f + c * (1.0f / 3.0f + c * 0.25f)));
-    const float e = c < 0.015625f ? series : -__logf(u);
-    return -__logf(e);
+    const float e = c < 0.015625f ? series : -fast_ln(u);
+    return -fast_ln(e);
 }
 
 struct Lane {
