@@ -34,13 +34,13 @@ METRIC = "decode-attn HBM GB/s (% of MI355X peak) + logprob/KL tokens/sec, 1 GPU
 PMC_TRAFFIC = {
     "logprob_kl": {"sources": ["logprob_kl.hip", "device_ops.h"],
                    "sha256": "deef495df77db1122d46065078daa6de157d2779e3dd3efc06e8985e2b872b76",
-                   "bytes": 67249695440 + 9243024},
+                   "bytes": 67249743059 + 8994904},
     "decode_attn": {"sources": ["attention.hip", "mfma_ops.h", "device_ops.h"],
                     "sha256": "66cc014f0071b48cb1d5568592032ea89776ecf42ec40852f392684dcb23eb36",
-                    "bytes": 1604497325 + 8513424 + 8987268 + 2097152},
+                    "bytes": 1604492041 + 8517880 + 8987338 + 2097152},
     "prefill_attn": {"sources": ["prefill.hip", "mfma_ops.h", "device_ops.h"],
                      "sha256": "a04d766941b9afcd95012d0b33ef9c6159fea53a4b2408f419ff7626d38e3f7e",
-                     "bytes": 4084290936 + 3322374512},
+                     "bytes": 4083956718 + 3322330576},
 }
 
 
