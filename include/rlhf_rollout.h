@@ -220,8 +220,8 @@ int rlhf_decode_attention(const rlhf_attn_params *params, const void *q, const v
 
 /* ------------------------------------------------------------------------
  * Fused token log-probability and actor-vs-reference KL (Section 2.1: actor
- * and reference inferences over the generated tokens; "minimizing policy
- * deviation").  For each position i, in one pass over the two logit rows:
+ * and reference inferences over the generated tokens; the KL term is what
+ * keeps the trained policy near the reference).  For each position i, in one pass over the two logit rows:
  *     logp_out[i] = log softmax(actor[i,:])[tokens[i]]
  *     kl_out[i]   = KL( softmax(actor[i,:]) || softmax(ref[i,:]) )   (nats, >= 0 up to rounding)
  * fp32 accumulation.  tokens[i] outside [0, vocab) marks padding: both
@@ -241,8 +241,8 @@ int rlhf_token_logprobs_kl(const void *actor_logits, const void *ref_logits, con
 
 /* ------------------------------------------------------------------------
  * The same pass with per-token reward shaping (Section 2.1: the reference
- * model is there "to prevent reward divergence", the reward model supplies the
- * sequence return).  Besides logp_out and kl_out, and at no extra HBM traffic:
+ * model is there to keep the reward from running away, the reward model
+ * supplies the sequence return).  Besides logp_out and kl_out, and at no extra HBM traffic:
  *     ref_logp_out[i] = log softmax(ref[i,:])[tokens[i]]
  *     reward_out[i]   = -kl_coef * penalty_i + terminal_scores[i]
  * with penalty_i = kl_out[i] (RLHF_PENALTY_FULL_KL) or the sampled estimate

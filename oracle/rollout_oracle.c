@@ -189,7 +189,7 @@ int oracle_decode_attention(const void *q, const void *k_pages, const void *v_pa
  * Per-position log-probability of the sampled token under the actor, and the
  * KL divergence of the actor's next-token distribution from the reference
  * model's (Section 2.1: the reference model restrains the policy; the actor is
- * trained while "minimizing policy deviation").  Natural logarithms.
+ * trained with its deviation from that policy penalised).  Natural logarithms.
  *
  *   actor, ref  [N][stride] rows, first V entries of each row used; storage dtype
  *   tokens      [N]
