@@ -759,6 +759,18 @@ def test_topk_draw_is_the_plain_draw_whenever_its_winner_survives(gu, cfg_index,
         assert (x[rows, tok.long()] >= tau).all()
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_topk_many_short_rows(gu, oracle, dtype):
+    """Thousands of rows of a small vocabulary (a scoring-sized call): one
+    workgroup per row, most lanes without an entry of their own."""
+    tdt = wl.torch_dtype(dtype)
+    g = torch.Generator(device=gu.DEV)
+    g.manual_seed(321)
+    logits = (torch.randn(3000, 777, generator=g, device=gu.DEV) * 2.5).to(tdt)
+    for k, T in ((5, 1.0), (300, 0.6), (776, 0.0)):
+        _check_topk(gu, oracle, logits, T, k, 8, 1)
+
+
 def test_topk_frequencies_on_the_gpu_follow_the_truncated_softmax(gu):
     import scipy.special
     import scipy.stats
