@@ -199,7 +199,7 @@ def test_prefill_is_bit_identical_under_page_permutation(gu):
     assert torch.equal(outs[0].view(torch.int32), outs[1].view(torch.int32))
 
 
-@pytest.mark.parametrize("cfg_index", [3, 5])
+@pytest.mark.parametrize("cfg_index", [3, 4, 5])
 def test_prefill_full_size_sampled_rows(gu, oracle, cfg_index):
     """The benchmark's prefill launch at the full shape; the oracle checks sampled
     rows one by one (first and last rows, page and block boundaries, seeded
@@ -220,7 +220,8 @@ def test_prefill_full_size_sampled_rows(gu, oracle, cfg_index):
         worst = 0.0
         for b in seqs:
             L = int(lens[b])
-            picks = sorted({0, 1, 15, 16, 31, 32, 255, 256, L - 1, L - 2, *rng.integers(0, L, 6).tolist()} & set(range(L)))
+            picks = sorted({0, 1, 15, 16, 31, 32, 47, 48, 255, 256, 383, 384, 767, 768, L - 1, L - 2,
+                            *rng.integers(0, L, 6).tolist()} & set(range(L)))
             kp, vp = wl.plain_pages([wl.to_storage(ks[b])], [wl.to_storage(vs[b])], table[b][None], A.n_pages)
             for p in picks:
                 expect = oracle.decode_attention(wl.to_storage(q[cu[b] + p][None]), kp, vp, table[b][None],
