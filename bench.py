@@ -33,14 +33,14 @@ METRIC = "decode-attn HBM GB/s (% of MI355X peak) + logprob/KL tokens/sec, 1 GPU
 # only while the kernel sources still hash to the value recorded with them.
 PMC_TRAFFIC = {
     "logprob_kl": {"sources": ["logprob_kl.hip", "device_ops.h"],
-                   "sha256": "deef495df77db1122d46065078daa6de157d2779e3dd3efc06e8985e2b872b76",
-                   "bytes": 67249743059 + 8994904},
+                   "sha256": "7a6e9c703b95bee5daffdc58a07c904c9d1435b613994793ba7dd2b2e02ec8e9",
+                   "bytes": 67249724675 + 8955832},
     "decode_attn": {"sources": ["attention.hip", "mfma_ops.h", "device_ops.h"],
                     "sha256": "66cc014f0071b48cb1d5568592032ea89776ecf42ec40852f392684dcb23eb36",
-                    "bytes": 1604492041 + 8517880 + 8987338 + 2097152},
+                    "bytes": 1604491785 + 8517016 + 8987369 + 2097152},
     "prefill_attn": {"sources": ["prefill.hip", "mfma_ops.h", "device_ops.h"],
                      "sha256": "a04d766941b9afcd95012d0b33ef9c6159fea53a4b2408f419ff7626d38e3f7e",
-                     "bytes": 4083956718 + 3322330576},
+                     "bytes": 4084417163 + 3322123221},
 }
 
 

@@ -190,9 +190,20 @@ __global__ __launch_bounds__(kThreads) void logprob_kl_kernel(
     RowSums st;
     if constexpr (VEC) {
         const int nvec = vocab / E;
+        // Rows whose byte length is not a multiple of 128 start off a 128-byte line
+        // every other row; then each wavefront's 1 KB load would straddle nine lines
+        // instead of eight.  The vectors before the first line boundary are taken
+        // by the first lanes, and the streaming loop starts on the boundary.
+        const int head = min((int)(((128u - (uint32_t)((uintptr_t)arow & 127u)) & 127u) >> 4), nvec);
+        if (tid < head) {
+            float fa[E], fr[E];
+            unpack_vec<DT>(load16((const uint4 *)arow + tid), fa);
+            unpack_vec<DT>(load16((const uint4 *)rrow + tid), fr);
+            accumulate<E>(st, fa, fr);
+        }
         const uint4 *pa = (const uint4 *)arow;
         const uint4 *pr = (const uint4 *)rrow;
-        int i = tid;
+        int i = head + tid;
         for (; i + (kUnroll - 1) * kThreads < nvec; i += kUnroll * kThreads) {
             uint4 va[kUnroll], vr[kUnroll];
 #pragma unroll
