@@ -33,14 +33,14 @@ METRIC = "decode-attn HBM GB/s (% of MI355X peak) + logprob/KL tokens/sec, 1 GPU
 # only while the kernel sources still hash to the value recorded with them.
 PMC_TRAFFIC = {
     "logprob_kl": {"sources": ["logprob_kl.hip", "device_ops.h"],
-                   "sha256": "7a6e9c703b95bee5daffdc58a07c904c9d1435b613994793ba7dd2b2e02ec8e9",
-                   "bytes": 67249724675 + 8955832},
+                   "sha256": "a1c9afe1c3b5699a7b70d09dcbf60deaa55d2f729d0a51b0c248d3537a73b1ad",
+                   "bytes": 67249754465 + 8957520},
     "decode_attn": {"sources": ["attention.hip", "mfma_ops.h", "device_ops.h"],
-                    "sha256": "66cc014f0071b48cb1d5568592032ea89776ecf42ec40852f392684dcb23eb36",
-                    "bytes": 1604491785 + 8517016 + 8987369 + 2097152},
+                    "sha256": "3038167cd47bb9fe59b8f058872c80516e2c04efabd33ac95a2651242277b1e0",
+                    "bytes": 1604492489 + 8514888 + 8987273 + 2097152},
     "prefill_attn": {"sources": ["prefill.hip", "mfma_ops.h", "device_ops.h"],
-                     "sha256": "a04d766941b9afcd95012d0b33ef9c6159fea53a4b2408f419ff7626d38e3f7e",
-                     "bytes": 4084417163 + 3322123221},
+                     "sha256": "ee01ae9803199f70b3ead4bf7233c8ca5b205e093f294f01571aca1762142593",
+                     "bytes": 4083248311 + 3322069813},
 }
 
 

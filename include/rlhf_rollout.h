@@ -37,6 +37,12 @@
  *     runs on the host at call time).
  *   - Compute entry points fail with RLHF_ERR_DEVICE when no HIP device is
  *     usable; there is no CPU fallback.
+ *   - One kernel launch holds fewer than 2^32 lanes per grid dimension.  The
+ *     row-wise entry points (log-prob/KL, the draws) spread rows over two
+ *     dimensions and take any int32 row count; the others return
+ *     RLHF_ERR_UNSUPPORTED, before anything has changed, for a call whose one
+ *     launch would not fit (the limits are stated with each: all are beyond
+ *     what fits the device's memory at the paper's model shapes).
  */
 #ifndef RLHF_ROLLOUT_H
 #define RLHF_ROLLOUT_H
@@ -53,7 +59,8 @@ typedef enum {
     RLHF_ERR_INVALID = -1,     /* NULL pointer, bad shape, id out of range, misaligned buffer */
     RLHF_ERR_OOM = -2,         /* arena has too few free pages; state unchanged */
     RLHF_ERR_DEVICE = -3,      /* a HIP call failed */
-    RLHF_ERR_UNSUPPORTED = -4  /* dtype / head_dim / page size outside what the kernels cover */
+    RLHF_ERR_UNSUPPORTED = -4  /* dtype / head_dim / page size outside what the kernels cover, or a
+                                  call too large for one launch (split it) */
 } rlhf_status;
 
 typedef enum { RLHF_F16 = 0, RLHF_BF16 = 1, RLHF_F32 = 2 } rlhf_dtype;
@@ -129,7 +136,9 @@ int rlhf_kv_arena_destroy(rlhf_kv_arena *arena);
  * [head_dim] in the arena's dtype, sequence after sequence.  A sequence id may
  * appear once per call.  All-or-nothing: if the free list is too short the call
  * returns RLHF_ERR_OOM, and if a sequence would outgrow max_pages_per_seq it
- * returns RLHF_ERR_INVALID; in both cases nothing has changed.  The host
+ * returns RLHF_ERR_INVALID; a call of more than 2^26 - 4 (token, head) pairs
+ * (sum n_new * n_kv_heads) returns RLHF_ERR_UNSUPPORTED; in all three cases
+ * nothing has changed.  The host
  * mirrors are updated before return; the device page table, lengths and K/V
  * pages are updated in stream order. */
 int rlhf_kv_arena_append(rlhf_kv_arena *arena, const int32_t *seq_ids /*host*/,
@@ -171,7 +180,8 @@ int rlhf_kv_arena_host_state(const rlhf_kv_arena *arena, const int32_t **page_ta
                              int32_t *free_count);
 
 /* Reads tokens [start, start+n) of a sequence back as plain rows: k_out / v_out
- * (dev) receive [n][n_kv_heads][head_dim] in the arena's dtype. */
+ * (dev) receive [n][n_kv_heads][head_dim] in the arena's dtype.  More than
+ * 2^26 - 4 (token, head) pairs in one call: RLHF_ERR_UNSUPPORTED. */
 int rlhf_kv_arena_gather(const rlhf_kv_arena *arena, int32_t seq_id, int32_t start, int32_t n,
                          void *k_out /*dev*/, void *v_out /*dev*/, void *stream);
 
@@ -196,7 +206,8 @@ int rlhf_kv_arena_gather(const rlhf_kv_arena *arena, int32_t seq_id, int32_t sta
  *   workspace  dev, >= rlhf_decode_attention_workspace_bytes, 16-byte aligned;
  *              scratch for split partials, contents undefined afterwards
  * q, k_arena, v_arena and out must be 16-byte aligned.  batch may not exceed
- * 8192 per call (RLHF_ERR_UNSUPPORTED; split larger batches).
+ * 8192 per call, nor batch * n_q_heads 2^26 - 4 (RLHF_ERR_UNSUPPORTED; split
+ * larger batches).
  * ------------------------------------------------------------------------ */
 typedef struct {
     int32_t batch;
@@ -232,6 +243,7 @@ int rlhf_decode_attention(const rlhf_attn_params *params, const void *q, const v
  *   tokens                    dev [n_positions] int32
  *   logp_out, kl_out          dev [n_positions] float
  *   row_stride_elems          0: vocab
+ *   n_positions               0 .. 2^31 - 1 (above: RLHF_ERR_INVALID)
  * Rows that start 16-byte aligned take the vectorised path; others a slower
  * element-wise one with the same results up to summation order.
  * ------------------------------------------------------------------------ */
@@ -283,6 +295,8 @@ int rlhf_token_logprobs_kl_rewards(const void *actor_logits, const void *ref_log
  *   log softmax(logits[i,:]/T)[token] (T = 1 for greedy).
  *   logits      dev [n_rows][row_stride_elems], F32 / BF16 / F16
  *   tokens_out  dev [n_rows] int32
+ *   n_rows      0 .. 2^31 - 1 (above: RLHF_ERR_INVALID); the row index is a 32-bit
+ *               counter word of the generator
  * ------------------------------------------------------------------------ */
 int rlhf_sample_tokens(const void *logits, int32_t *tokens_out, float *logp_out, int64_t n_rows,
                        int32_t vocab, int64_t row_stride_elems, int32_t logits_dtype, float temperature,

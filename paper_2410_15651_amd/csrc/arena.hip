@@ -456,6 +456,11 @@ extern "C" int rlhf_kv_arena_append(rlhf_kv_arena *arena, const int32_t *seq_ids
             return fail(RLHF_ERR_INVALID, "NULL k_new / v_new");
         if (((uintptr_t)k_new | (uintptr_t)v_new) % 16)
             return fail(RLHF_ERR_INVALID, "k_new / v_new must be 16-byte aligned");
+        // every copy kernel below takes one wavefront per (token or page, head):
+        // tokens x heads bounds all three grids
+        if ((total * arena->desc.n_kv_heads + 3) / 4 > max_workgroups(256))
+            return fail(RLHF_ERR_UNSUPPORTED, "append of %lld tokens x %d heads is too large for one launch: split the call",
+                        (long long)total, arena->desc.n_kv_heads);
     }
     const ArenaBook::Result r = arena->book->append(seq_ids, n_new, n_seqs, &arena->plan);
     if (r == ArenaBook::kOom)
@@ -509,7 +514,7 @@ extern "C" int rlhf_kv_arena_append(rlhf_kv_arena *arena, const int32_t *seq_ids
     w[2] = n_desc;
     w[3] = 0;
     const int64_t heads = arena->desc.n_kv_heads;
-    if (whole_pages == 0 && edge_tokens == n_desc && ((int64_t)n_desc * heads + 3) / 4 <= 0x7fffffffLL) {
+    if (whole_pages == 0 && edge_tokens == n_desc) {
         // a decode step: one token per sequence, placed and booked by one launch
         // (a sequence gets at most one new page, so the grid covers the table changes)
         hipLaunchKernelGGL(kv_append_step_kernel, dim3((unsigned)(((int64_t)n_desc * heads + 3) / 4)), dim3(256),
@@ -526,8 +531,6 @@ extern "C" int rlhf_kv_arena_append(rlhf_kv_arena *arena, const int32_t *seq_ids
     if (rc != RLHF_OK)
         return rc;
 
-    if ((whole_pages * heads + 3) / 4 > 0x7fffffffLL || (edge_tokens * heads + 3) / 4 > 0x7fffffffLL)
-        return fail(RLHF_ERR_INVALID, "append too large for one launch");
     if (whole_pages > 0) {
         hipLaunchKernelGGL(kv_scatter_pages_kernel, dim3((unsigned)((whole_pages * heads + 3) / 4)), dim3(256), 0, s,
                            (const uint16_t *)k_new, (const uint16_t *)v_new, (uint16_t *)arena->kv,
@@ -657,6 +660,9 @@ extern "C" int rlhf_kv_arena_gather(const rlhf_kv_arena *arena, int32_t seq_id, 
     if (!k_out || !v_out || ((uintptr_t)k_out | (uintptr_t)v_out) % 16)
         return fail(RLHF_ERR_INVALID, "k_out / v_out must be non-NULL and 16-byte aligned");
     const int64_t items = (int64_t)n * arena->desc.n_kv_heads;
+    if ((items + 3) / 4 > max_workgroups(256))
+        return fail(RLHF_ERR_UNSUPPORTED, "gather of %d tokens x %d heads is too large for one launch: split the call",
+                    n, arena->desc.n_kv_heads);
     hipLaunchKernelGGL(kv_gather_kernel, dim3((unsigned)((items + 3) / 4)), dim3(256), 0, (hipStream_t)stream,
                        (const uint16_t *)arena->kv, (const uint16_t *)(arena->kv + arena->half_bytes),
                        (uint16_t *)k_out, (uint16_t *)v_out,

@@ -656,6 +656,8 @@ int check_params(const rlhf_attn_params *p)
     if ((int64_t)p->max_pages_per_seq * kPage > 0x7fffffffLL ||
         (int64_t)p->batch * p->max_pages_per_seq > 0x7fffffffLL)
         return fail(RLHF_ERR_INVALID, "page table too large");
+    if ((int64_t)p->batch * p->n_q_heads > 4 * max_workgroups(256))  // merge: one wavefront per (sequence, head)
+        return fail(RLHF_ERR_UNSUPPORTED, "batch x n_q_heads too large for one launch: split the call");
     return RLHF_OK;
 }
 

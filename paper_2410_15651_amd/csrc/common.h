@@ -22,6 +22,27 @@ inline int elem_bytes(int dtype)
     return dtype == RLHF_F32 ? 4 : 2;
 }
 
+// The runtime forms a launch's size per grid dimension as workgroups x lanes
+// in 32 bits and reports no error when that wraps (a grid of 2^24 + 3
+// workgroups of 256 lanes runs three of them).  Every launch keeps each
+// dimension at or below this count.
+constexpr int64_t max_workgroups(int lanes_per_workgroup)
+{
+    return 0xffffffffLL / lanes_per_workgroup;
+}
+
+// Kernels with one workgroup per row spread the rows over grid.x and grid.y:
+// row = blockIdx.y * kRowSlab + blockIdx.x, and workgroups past the last row
+// leave at once.  2^20 x 1024 lanes stays below the 32-bit limit and 65,535
+// slabs cover any int32 row count.
+constexpr int64_t kRowSlab = 1 << 20;
+
+inline dim3 row_grid(int64_t n_rows, unsigned z = 1)
+{
+    const int64_t x = n_rows < kRowSlab ? n_rows : kRowSlab;
+    return dim3((unsigned)x, (unsigned)((n_rows + kRowSlab - 1) / kRowSlab), z);
+}
+
 }  // namespace rlhf
 
 #define RLHF_HIP_TRY(expr)                                                                 \

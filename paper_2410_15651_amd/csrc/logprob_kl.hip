@@ -155,10 +155,13 @@ struct Shaping {
 template <int DT, bool VEC>
 __global__ __launch_bounds__(kThreads) void logprob_kl_kernel(
     const void *__restrict__ actor, const void *__restrict__ ref, const int32_t *__restrict__ tokens,
-    float *__restrict__ logp_out, float *__restrict__ kl_out, int vocab, int64_t stride, Shaping sh)
+    float *__restrict__ logp_out, float *__restrict__ kl_out, int64_t n_rows, int vocab, int64_t stride,
+    Shaping sh)
 {
     __shared__ float lds[kWaves];
-    const int64_t row = blockIdx.x;
+    const int64_t row = (int64_t)blockIdx.y * kRowSlab + blockIdx.x;
+    if (row >= n_rows)  // the last slab of a grid of more than kRowSlab rows
+        return;
     const int tid = threadIdx.x;
     const int tok = tokens[row];
     if (tok < 0 || tok >= vocab) {  // padded position: uniform across the block
@@ -271,13 +274,13 @@ template <int DT>
 int launch(const void *actor, const void *ref, const int32_t *tokens, float *logp, float *kl,
            int64_t n, int vocab, int64_t stride, bool vec, const Shaping &sh, hipStream_t s)
 {
-    const dim3 grid((unsigned)n), block(kThreads);
+    const dim3 grid = row_grid(n), block(kThreads);
     if (vec)
         hipLaunchKernelGGL((logprob_kl_kernel<DT, true>), grid, block, 0, s, actor, ref, tokens, logp,
-                           kl, vocab, stride, sh);
+                           kl, n, vocab, stride, sh);
     else
         hipLaunchKernelGGL((logprob_kl_kernel<DT, false>), grid, block, 0, s, actor, ref, tokens, logp,
-                           kl, vocab, stride, sh);
+                           kl, n, vocab, stride, sh);
     RLHF_LAUNCH_CHECK("logprob_kl_kernel");
     return RLHF_OK;
 }

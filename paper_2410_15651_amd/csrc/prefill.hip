@@ -369,7 +369,7 @@ int launch_waves(const rlhf_attn_params &p, const void *q, const int32_t *cu_q, 
     const int n_blocks = (max_q_len + pos_per_wg - 1) / pos_per_wg;
     const int64_t units = (int64_t)p.batch * p.n_kv_heads;
     const int64_t grid = (units + kXcds - 1) / kXcds * kXcds * n_blocks;
-    if (grid > 0x7fffffffLL)
+    if (grid > max_workgroups(WAVES * 64))
         return fail(RLHF_ERR_UNSUPPORTED, "prefill launch of %lld workgroups: split the call", (long long)grid);
     const int cap = p.max_pages_per_seq * kPage;
     const int max_len = (p.max_seq_len > 0 && p.max_seq_len < cap) ? p.max_seq_len : cap;

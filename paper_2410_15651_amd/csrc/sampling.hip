@@ -152,20 +152,23 @@ struct SegmentRecord {
     float s;
 };
 
-// Workgroup (x, y) takes segment y of gridDim.y of row x.  With one segment it
-// writes the row's results; with more it writes its record to `records`
-// [row][segment].
+// Workgroup (x, y, z) takes segment z of gridDim.z of row y * kRowSlab + x.  With
+// one segment it writes the row's results; with more it writes its record to
+// `records` [row][segment].
 template <int DT, bool VEC, bool NOISE, bool LSE, int kThreads>
 __global__ __launch_bounds__(kThreads) void sample_tokens_kernel(
     const void *__restrict__ logits, int32_t *__restrict__ tokens_out, float *__restrict__ logp_out,
-    SegmentRecord *__restrict__ records, int vocab, int64_t stride, float inv_t, uint2 key, uint2 off)
+    SegmentRecord *__restrict__ records, int64_t n_rows, int vocab, int64_t stride, float inv_t, uint2 key,
+    uint2 off)
 {
     constexpr int kWaves = kThreads / 64;
     __shared__ float s_f[kWaves];
     __shared__ int s_i[kWaves];
-    const int64_t row64 = blockIdx.x;
+    const int64_t row64 = (int64_t)blockIdx.y * kRowSlab + blockIdx.x;
+    if (row64 >= n_rows)  // the last slab of a grid of more than kRowSlab rows
+        return;
     const uint32_t row = (uint32_t)row64;
-    const int seg = blockIdx.y, n_seg = gridDim.y;
+    const int seg = blockIdx.z, n_seg = gridDim.z;
     const int tid = threadIdx.x;
     constexpr int EB = (DT == RLHF_F32) ? 4 : 2;
     const char *base = (const char *)logits + row64 * stride * EB;
@@ -413,15 +416,17 @@ __device__ __forceinline__ void row_foreach(const char *base, int vocab, int tid
 // that): the kernel has to stay well inside the instruction cache.
 template <int DT, bool VEC, bool NOISE>
 __global__ __launch_bounds__(kTopkThreads) void sample_topk_kernel(
-    const void *__restrict__ logits, int32_t *__restrict__ tokens_out, float *__restrict__ logp_out, int vocab,
-    int64_t stride, int top_k, float inv_t, uint2 key, uint2 off)
+    const void *__restrict__ logits, int32_t *__restrict__ tokens_out, float *__restrict__ logp_out,
+    int64_t n_rows, int vocab, int64_t stride, int top_k, float inv_t, uint2 key, uint2 off)
 {
     __shared__ uint32_t s_key[kTopkCap];
     __shared__ int s_idx[kTopkCap];
     __shared__ uint32_t s_top[kTopkWaves], s_low[kTopkWaves], s_cnt[2][kTopkWaves], s_i[kTopkWaves];
     __shared__ float s_f[kTopkWaves], s_r[kTopkWaves], s_s[kTopkWaves];
     __shared__ int s_fill;
-    const int64_t row64 = blockIdx.x;
+    const int64_t row64 = (int64_t)blockIdx.y * kRowSlab + blockIdx.x;
+    if (row64 >= n_rows)  // the last slab of a grid of more than kRowSlab rows
+        return;
     const uint32_t row = (uint32_t)row64;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     constexpr int EB = (DT == RLHF_F32) ? 4 : 2;
@@ -702,10 +707,10 @@ int launch_topk(const void *logits, int32_t *tokens, float *logp, int64_t n, int
     const uint2 off = make_uint2((uint32_t)offset, (uint32_t)(offset >> 32));
     const bool noise = temperature > 0.f;
     const float inv_t = noise ? 1.0f / temperature : 1.0f;
-    const dim3 grid((unsigned)n), block(kTopkThreads);
-#define RLHF_TOPK_LAUNCH(V, N)                                                                               \
-    hipLaunchKernelGGL((sample_topk_kernel<DT, V, N>), grid, block, 0, s, logits, tokens, logp, vocab, stride, \
-                       top_k, inv_t, key, off)
+    const dim3 grid = row_grid(n), block(kTopkThreads);
+#define RLHF_TOPK_LAUNCH(V, N)                                                                          \
+    hipLaunchKernelGGL((sample_topk_kernel<DT, V, N>), grid, block, 0, s, logits, tokens, logp, n, vocab, \
+                       stride, top_k, inv_t, key, off)
     if (vec && noise)
         RLHF_TOPK_LAUNCH(true, true);
     else if (vec)
@@ -739,7 +744,7 @@ int launch(const void *logits, int32_t *tokens, float *logp, int64_t n, int voca
 {
     const int n_seg = segments(n, vocab, workspace != nullptr);
     SegmentRecord *records = (SegmentRecord *)workspace;
-    const dim3 grid((unsigned)n, (unsigned)n_seg);
+    const dim3 grid = row_grid(n, (unsigned)n_seg);
     const uint2 key = make_uint2((uint32_t)seed, (uint32_t)(seed >> 32));
     const uint2 off = make_uint2((uint32_t)offset, (uint32_t)(offset >> 32));
     const bool noise = temperature > 0.f;
@@ -750,10 +755,10 @@ int launch(const void *logits, int32_t *tokens, float *logp, int64_t n, int voca
     do {                                                                                                       \
         if (lse)                                                                                               \
             hipLaunchKernelGGL((sample_tokens_kernel<DT, V, N, true, T>), grid, dim3(T), 0, s, logits, tokens, \
-                               logp, records, vocab, stride, inv_t, key, off);                                 \
+                               logp, records, n, vocab, stride, inv_t, key, off);                              \
         else                                                                                                   \
             hipLaunchKernelGGL((sample_tokens_kernel<DT, V, N, false, T>), grid, dim3(T), 0, s, logits, tokens, \
-                               logp, records, vocab, stride, inv_t, key, off);                                 \
+                               logp, records, n, vocab, stride, inv_t, key, off);                              \
     } while (0)
 #define RLHF_SAMPLE_PICK(V, N)          \
     do {                                \

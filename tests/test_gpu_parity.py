@@ -148,6 +148,30 @@ def test_arena_appends_that_mix_edge_tokens_and_whole_pages(gu, dtype, head_dim)
         rb.rlhf_kv_arena_destroy(arena)
 
 
+def test_arena_append_too_large_for_one_launch_is_refused(gu):
+    """The copy kernels take one wavefront per (token, head), four to a
+    workgroup of 256 lanes; past 2^32 lanes a launch's size no longer fits the
+    runtime's 32 bits.  Such a call is refused before the bookkeeping moves."""
+    heads = 32
+    arena = rb.rlhf_kv_arena_create(max_seqs=2, n_kv_heads=heads, head_dim=64, n_pages=8, max_pages_per_seq=4,
+                                    kv_dtype=wl.DTYPE_CODE["bf16"])
+    try:
+        dummy = torch.zeros(P, heads, 64, dtype=torch.bfloat16, device=gu.DEV)
+        rb.rlhf_kv_arena_append(arena, [1], [P], dummy, dummy)
+        before = rb.rlhf_kv_arena_stats(arena)
+        with pytest.raises(rb.RlhfError) as e:
+            rb.rlhf_kv_arena_append(arena, [0], [1 << 21], dummy, dummy)     # 2^21 tokens x 32 heads / 4 = 2^24
+        assert e.value.status == rb.RLHF_ERR_UNSUPPORTED
+        assert rb.rlhf_kv_arena_stats(arena) == before
+        rb.rlhf_kv_arena_append(arena, [0], [3], dummy, dummy)              # the arena still works
+        ko, vo = torch.ones_like(dummy[:3]), torch.ones_like(dummy[:3])
+        rb.rlhf_kv_arena_gather(arena, 0, 0, 3, ko, vo)
+        torch.cuda.synchronize()
+        assert not ko.any() and not vo.any()
+    finally:
+        rb.rlhf_kv_arena_destroy(arena)
+
+
 # -------------------------------------------------------------- attention ----
 SMALL_ATTN = [
     # (config index, overrides) -- shapes span several pages, chunks and a ragged tail
@@ -769,6 +793,41 @@ def test_topk_many_short_rows(gu, oracle, dtype):
     logits = (torch.randn(3000, 777, generator=g, device=gu.DEV) * 2.5).to(tdt)
     for k, T in ((5, 1.0), (300, 0.6), (776, 0.0)):
         _check_topk(gu, oracle, logits, T, k, 8, 1)
+
+
+@pytest.mark.parametrize("n", [(1 << 20) + 5, (1 << 24) + 3])
+def test_row_counts_past_one_grid_dimension(gu, oracle, n):
+    """One workgroup per row.  2^20 rows fill the grid's first dimension, and
+    2^24 workgroups of 256 lanes are where the size of a one-dimensional launch
+    no longer fits 32 bits: every row must still be scored and drawn, with the
+    noise of its own row index."""
+    V = 4
+    g = torch.Generator(device=gu.DEV)
+    g.manual_seed(n)
+    actor = torch.randn(n, V, generator=g, device=gu.DEV) * 2.0
+    ref = torch.randn(n, V, generator=g, device=gu.DEV) * 2.0
+    tok = torch.randint(0, V, (n,), generator=g, device=gu.DEV, dtype=torch.int32).cpu().numpy()
+    _say(f"logprob n={n} V={V} f32")
+    logp, kl = gu.run_logprobs(actor, ref, tok)
+    el, ek = oracle.token_logprobs_kl(wl.to_storage(actor), wl.to_storage(ref), tok, wl.DTYPE_CODE["f32"])
+    assert np.abs(logp - el).max() <= LOGP_TOL
+    assert np.abs(kl - ek).max() <= LOGP_TOL
+    del ref
+    _say(f"plain draw n={n}")
+    got, agree, clear = _check_sampling(gu, oracle, actor, 1.0, 77, 3)
+    assert agree > 0.999
+
+
+@pytest.mark.parametrize("n", [(1 << 20) + 5, (1 << 22) + 3])
+def test_topk_row_counts_past_one_grid_dimension(gu, oracle, n):
+    """As above for the 1024-lane top-k kernel, whose one-dimensional launch
+    would stop fitting 32 bits at 2^22 rows."""
+    g = torch.Generator(device=gu.DEV)
+    g.manual_seed(n)
+    logits = torch.randn(n, 4, generator=g, device=gu.DEV) * 2.0
+    _say(f"top-2 draw n={n}")
+    got, agree, count = _check_topk(gu, oracle, logits, 1.0, 2, 78, 5)
+    assert agree > 0.999
 
 
 def test_topk_frequencies_on_the_gpu_follow_the_truncated_softmax(gu):
