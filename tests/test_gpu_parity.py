@@ -185,6 +185,9 @@ SMALL_ATTN = [
     (2, dict(batch=3, n_q_heads=8, n_kv_heads=4, len_lo=100, len_hi=400)),            # group of 2
     (3, dict(batch=2, n_q_heads=48, n_kv_heads=2, len_lo=30, len_hi=900)),            # group of 24 > 16
     (1, dict(batch=2, n_q_heads=32, n_kv_heads=2, len_lo=200, len_hi=700)),           # f16, group of 16
+    # long contexts: tens of thousands of pages per sequence, far more page steps than wavefronts
+    (2, dict(batch=2, n_q_heads=2, n_kv_heads=2, len_lo=150000, len_hi=300000)),
+    (5, dict(batch=1, n_q_heads=8, n_kv_heads=1, len_lo=200003, len_hi=200003)),
 ]
 
 

@@ -88,6 +88,7 @@ SMALL = [
     (4, dict(batch=2, n_q_heads=6, n_kv_heads=2, len_lo=90, len_hi=200), "full"),      # group of 3: idle columns
     (3, dict(batch=2, n_q_heads=48, n_kv_heads=2, len_lo=30, len_hi=120), "chunk"),    # group of 24
     (1, dict(batch=2, n_q_heads=32, n_kv_heads=2, head_dim=128, len_lo=33, len_hi=90), "full"),   # f16, group of 16
+    (2, dict(batch=1, n_q_heads=4, n_kv_heads=4, len_lo=3001, len_hi=3001), "full"),   # a long prompt: 8+ blocks of rows
     (5, dict(batch=2, n_q_heads=8, n_kv_heads=2, head_dim=64, len_lo=1, len_hi=50), "full"),
 ]
 
