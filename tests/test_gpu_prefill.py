@@ -239,3 +239,39 @@ def test_prefill_full_size_sampled_rows(gu, oracle, cfg_index):
         assert (o >= vmin[None, :, None, :] - 1e-5).all() and (o <= vmax[None, :, None, :] + 1e-5).all()
     finally:
         A.close()
+
+
+def test_pages_beyond_4_gib_of_an_arena_half(gu, oracle):
+    """K and V halves of 4.6 GiB each, the sequences' pages scattered over all of
+    them by the shuffled free list: block offsets inside a half need more than
+    32 bits in the append, the read-back, decode attention and prefill."""
+    cfg = wl.small_variant(wl.config(5), batch=3, n_q_heads=16, n_kv_heads=8, len_lo=100, len_hi=600)
+    lens = wl.seq_lengths(cfg)
+    q1, ks, vs = wl.qkv(cfg, lens, device=gu.DEV)
+    _say(f"large arena: lens={lens.tolist()}")
+    A = gu.FilledArena(cfg, lens, ks, vs, slack_pages=150000)
+    try:
+        table, _, _ = A.host_state()
+        half_page_bytes = cfg.n_kv_heads * P * cfg.head_dim * 2
+        beyond = int((table.astype(np.int64) * half_page_bytes >= 2 ** 32).sum())
+        _say(f"  {beyond} of {int((table >= 0).sum())} pages start beyond 4 GiB")
+        assert beyond >= 3
+        # the oracle gets the same pages under compact numbers (the arena's own run to 150,000)
+        used = np.unique(table[table >= 0])
+        compact = np.where(table >= 0, np.searchsorted(used, table), -1).astype(np.int32)
+        for b in range(cfg.batch):
+            ko, vo = torch.zeros_like(ks[b]), torch.zeros_like(vs[b])
+            rb.rlhf_kv_arena_gather(A.handle, b, 0, int(lens[b]), ko, vo)
+            torch.cuda.synchronize()
+            assert torch.equal(ko.view(torch.int16), ks[b].view(torch.int16))
+            assert torch.equal(vo.view(torch.int16), vs[b].view(torch.int16))
+        expect = gu.oracle_attention(oracle, cfg, q1, ks, vs, compact, lens, len(used))
+        out = gu.run_attention(cfg, A, q1, out_dtype=rb.RLHF_F32).cpu().numpy().astype(np.float64)
+        assert np.abs(out - expect).max() <= ATTN_TOL
+        cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+        q = wl.query_rows(cfg, int(cu[-1]), device=gu.DEV)
+        expect = _oracle(oracle, cfg, q, cu, ks, vs, compact, lens, len(used))
+        outp = _run(gu, cfg, A, q, cu, int(lens.max()), out_dtype=rb.RLHF_F32).cpu().numpy().astype(np.float64)
+        assert np.abs(outp - expect).max() <= ATTN_TOL
+    finally:
+        A.close()
