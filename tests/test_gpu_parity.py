@@ -798,6 +798,34 @@ def test_topk_many_short_rows(gu, oracle, dtype):
         _check_topk(gu, oracle, logits, T, k, 8, 1)
 
 
+@pytest.mark.parametrize("dtype,vocab,stride", [("bf16", 3000017, 3000024), ("f32", 2500003, 2500003)])
+def test_rows_of_millions_of_entries(gu, oracle, dtype, vocab, stride):
+    """Rows far longer than any vocabulary of the paper's models (vector path
+    with a ragged tail, and the element-wise path of an odd stride): scoring,
+    the plain draw whole and in segments, top-k with an on-chip list, with a
+    list too long for it, and with half the row surviving."""
+    n = 3
+    g = torch.Generator(device=gu.DEV)
+    g.manual_seed(vocab)
+    tdt = wl.torch_dtype(dtype)
+    actor = (torch.randn(n, stride, generator=g, device=gu.DEV) * 3.0).to(tdt)
+    ref = (torch.randn(n, stride, generator=g, device=gu.DEV) * 3.0).to(tdt)
+    tok = np.array([0, vocab - 1, vocab // 2], dtype=np.int32)
+    _say(f"logprob V={vocab} stride={stride} {dtype}")
+    logp, kl = gu.run_logprobs(actor, ref, tok, vocab=vocab, stride=stride)
+    el, ek = oracle.token_logprobs_kl(wl.to_storage(actor), wl.to_storage(ref), tok, wl.DTYPE_CODE[dtype],
+                                      vocab=vocab)
+    assert np.abs(logp - el).max() <= LOGP_TOL
+    assert np.abs(kl - ek).max() <= LOGP_TOL
+    del ref
+    _say("  plain draw")
+    _check_sampling(gu, oracle, actor, 1.0, 5, 9, vocab=vocab, stride=stride)
+    _check_sampling(gu, oracle, actor, 0.8, 5, 9, vocab=vocab, stride=stride, split=True)
+    for k in (50, 70000, vocab // 2):
+        _say(f"  top-{k}")
+        _check_topk(gu, oracle, actor, 1.0, k, 6, 2, vocab=vocab, stride=stride)
+
+
 @pytest.mark.parametrize("n", [(1 << 20) + 5, (1 << 24) + 3])
 def test_row_counts_past_one_grid_dimension(gu, oracle, n):
     """One workgroup per row.  2^20 rows fill the grid's first dimension, and
