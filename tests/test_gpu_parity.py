@@ -148,6 +148,68 @@ def test_arena_appends_that_mix_edge_tokens_and_whole_pages(gu, dtype, head_dim)
         rb.rlhf_kv_arena_destroy(arena)
 
 
+def test_arena_with_a_hundred_thousand_sequences(gu):
+    """Descriptor lists of 100,000 entries through the one-launch decode step,
+    through the general path (edge tokens and whole pages in one call) and
+    through a step again; bookkeeping against the Python model, rows read back
+    from sampled sequences and the device mirrors against the host's."""
+    from oracle import ArenaModel
+    S, H, D = 100_000, 2, 64
+    rng = np.random.default_rng(99)
+    grow = rng.integers(0, 40, S).astype(np.int32)          # tokens of the middle call; a third stay away
+    grow[rng.random(S) < 0.33] = 0
+    n_pages = int(((2 + grow.astype(np.int64) + P - 1) // P).sum()) + 7
+    mpps = 3
+    order = rng.permutation(n_pages).astype(np.int32)
+    arena = rb.rlhf_kv_arena_create(max_seqs=S, n_kv_heads=H, head_dim=D, n_pages=n_pages, max_pages_per_seq=mpps,
+                                    kv_dtype=wl.DTYPE_CODE["f16"], initial_free_order=order)
+    model = ArenaModel(S, H, D, P, n_pages, mpps, initial_free_order=order)
+    try:
+        g = torch.Generator(device=gu.DEV)
+        g.manual_seed(5)
+        calls = [(np.arange(S, dtype=np.int32), np.ones(S, dtype=np.int32)),
+                 (np.nonzero(grow)[0].astype(np.int32)[::-1].copy(), grow[np.nonzero(grow)[0]][::-1].copy()),
+                 (np.arange(S, dtype=np.int32), np.ones(S, dtype=np.int32))]
+        rows_k = [[] for _ in range(S)]
+        rows_v = [[] for _ in range(S)]
+        watch = set(rng.choice(S, 60, replace=False).tolist()) | {0, S - 1}
+        for ids, cnt in calls:
+            total = int(cnt.sum())
+            _say(f"append of {total} tokens to {len(ids)} sequences")
+            k_new = torch.randn(total, H, D, generator=g, device=gu.DEV).to(torch.float16)
+            v_new = torch.randn(total, H, D, generator=g, device=gu.DEV).to(torch.float16)
+            rb.rlhf_kv_arena_append(arena, ids, cnt, k_new, v_new)
+            model.append(ids.tolist(), cnt.tolist())
+            off = np.concatenate([[0], np.cumsum(cnt)])
+            for i, b in enumerate(ids.tolist()):
+                if b in watch:
+                    rows_k[b].append(k_new[off[i]:off[i + 1]])
+                    rows_v[b].append(v_new[off[i]:off[i + 1]])
+        torch.cuda.synchronize()
+        table, hl, free = rb.rlhf_kv_arena_host_state(arena, S, mpps)
+        assert hl.tolist() == model.seq_lens == (2 + grow).tolist()
+        assert table.tolist() == model.page_table() and free.tolist() == model.free
+        _, _, d_table, d_lens = rb.rlhf_kv_arena_views(arena)
+        import ctypes
+        hip = ctypes.CDLL("libamdhip64.so")
+        dev_table = torch.empty(S * mpps, dtype=torch.int32, device=gu.DEV)
+        dev_lens = torch.empty(S, dtype=torch.int32, device=gu.DEV)
+        assert hip.hipMemcpy(ctypes.c_void_p(dev_table.data_ptr()), ctypes.c_void_p(d_table),
+                             ctypes.c_size_t(S * mpps * 4), 3) == 0
+        assert hip.hipMemcpy(ctypes.c_void_p(dev_lens.data_ptr()), ctypes.c_void_p(d_lens), ctypes.c_size_t(S * 4), 3) == 0
+        assert np.array_equal(dev_table.cpu().numpy().reshape(S, mpps), table)
+        assert np.array_equal(dev_lens.cpu().numpy(), hl)
+        for b in sorted(watch):
+            ek, ev = torch.cat(rows_k[b]), torch.cat(rows_v[b])
+            ko, vo = torch.zeros_like(ek), torch.zeros_like(ev)
+            rb.rlhf_kv_arena_gather(arena, b, 0, int(hl[b]), ko, vo)
+            torch.cuda.synchronize()
+            assert torch.equal(ko.view(torch.int16), ek.view(torch.int16)), b
+            assert torch.equal(vo.view(torch.int16), ev.view(torch.int16)), b
+    finally:
+        rb.rlhf_kv_arena_destroy(arena)
+
+
 def test_arena_append_too_large_for_one_launch_is_refused(gu):
     """The copy kernels take one wavefront per (token, head), four to a
     workgroup of 256 lanes; past 2^32 lanes a launch's size no longer fits the
