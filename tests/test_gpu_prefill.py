@@ -275,3 +275,27 @@ def test_pages_beyond_4_gib_of_an_arena_half(gu, oracle):
         assert np.abs(outp - expect).max() <= ATTN_TOL
     finally:
         A.close()
+
+
+def test_prefill_of_thousands_of_short_prompts(gu, oracle):
+    """A scoring-sized batch: 3,001 sequences of 0 to 40 tokens, three KV heads
+    (units per launch not a multiple of the chip's eight dies), one position
+    block each, most of it empty."""
+    cfg = wl.small_variant(wl.config(2), batch=3001, n_q_heads=6, n_kv_heads=3, len_lo=0, len_hi=40)
+    lens = wl.seq_lengths(cfg)
+    lens[0] = 0
+    lens[-1] = 40
+    n_new = lens.copy()
+    n_new[5::7] = np.minimum(n_new[5::7], 3)            # some sequences score only their last tokens
+    cu = np.concatenate([[0], np.cumsum(n_new)]).astype(np.int32)
+    _, ks, vs = wl.qkv(cfg, lens, device=gu.DEV)
+    q = wl.query_rows(cfg, int(cu[-1]), device=gu.DEV)
+    A = gu.FilledArena(cfg, lens, ks, vs)
+    try:
+        table, _, _ = A.host_state()
+        expect = _oracle(oracle, cfg, q, cu, ks, vs, table, lens, A.n_pages)
+        out = _run(gu, cfg, A, q, cu, int(n_new.max()), out_dtype=rb.RLHF_F32)
+        assert torch.isfinite(out).all()
+        assert np.abs(out.cpu().numpy().astype(np.float64) - expect).max() <= ATTN_TOL
+    finally:
+        A.close()
