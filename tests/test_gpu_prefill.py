@@ -299,3 +299,27 @@ def test_prefill_of_thousands_of_short_prompts(gu, oracle):
         assert np.abs(out.cpu().numpy().astype(np.float64) - expect).max() <= ATTN_TOL
     finally:
         A.close()
+
+
+def test_lengths_above_max_seq_len_count_as_max_seq_len(gu, oracle):
+    """The documented clamp, for the decode step and for prefill: a sequence
+    longer than params.max_seq_len is attended as if it ended there."""
+    cfg = wl.small_variant(wl.config(3), batch=5, n_q_heads=4, n_kv_heads=2, len_lo=0, len_hi=130)
+    lens = np.array([130, 37, 48, 49, 5], dtype=np.int32)
+    cap = 48
+    clipped = np.minimum(lens, cap).astype(np.int32)
+    q1, ks, vs = wl.qkv(cfg, lens, device=gu.DEV)
+    A = gu.FilledArena(cfg, lens, ks, vs)
+    try:
+        table, _, _ = A.host_state()
+        expect = gu.oracle_attention(oracle, cfg, q1, ks, vs, table, clipped, A.n_pages)
+        out = gu.run_attention(cfg, A, q1, out_dtype=rb.RLHF_F32, max_seq_len=cap).cpu().numpy().astype(np.float64)
+        assert np.abs(out - expect).max() <= ATTN_TOL
+        n_new = np.array([48, 7, 20, 1, 5], dtype=np.int32)       # rows are the last ones of the clamped cache
+        cu = np.concatenate([[0], np.cumsum(n_new)]).astype(np.int32)
+        q = wl.query_rows(cfg, int(cu[-1]), device=gu.DEV)
+        expect = _oracle(oracle, cfg, q, cu, ks, vs, table, clipped, A.n_pages)
+        outp = _run(gu, cfg, A, q, cu, 48, out_dtype=rb.RLHF_F32, max_seq_len=cap)
+        assert np.abs(outp.cpu().numpy().astype(np.float64) - expect).max() <= ATTN_TOL
+    finally:
+        A.close()
