@@ -148,6 +148,50 @@ def test_arena_appends_that_mix_edge_tokens_and_whole_pages(gu, dtype, head_dim)
         rb.rlhf_kv_arena_destroy(arena)
 
 
+def test_arena_reset_between_two_generations(gu, oracle):
+    """The phase boundary of the paper's pipeline: a generation fills the arena,
+    reset returns every page in the initial order, and the next generation's
+    sequences (other lengths) see none of the old state on the device."""
+    cfg = wl.small_variant(wl.config(5), batch=5, n_q_heads=8, n_kv_heads=2, len_lo=20, len_hi=200)
+    lens1 = wl.seq_lengths(cfg)
+    q, ks, vs = wl.qkv(cfg, lens1, device=gu.DEV)
+    A = gu.FilledArena(cfg, lens1, ks, vs, slack_pages=9)
+    try:
+        reserved = rb.rlhf_kv_arena_stats(A.handle)["reserved_bytes"]
+        rb.rlhf_kv_arena_reset(A.handle)
+        A.model.reset()
+        st = rb.rlhf_kv_arena_stats(A.handle)
+        assert st["pages_in_use"] == 0 and st["allocated_bytes"] == 0 and st["reserved_bytes"] == reserved
+        table, hl, free = A.host_state()
+        assert (table == -1).all() and not hl.any() and free.tolist() == A.model.free == A.order.tolist()
+        lens2 = np.array([33, 0, 150, 16, 1], dtype=np.int32)       # fits: every sequence shorter than len_hi
+        q2, ks2, vs2 = wl.qkv(cfg, lens2, device=gu.DEV, seed=cfg.seed + 1)
+        ids = [4, 2, 0, 3]
+        rb.rlhf_kv_arena_append(A.handle, ids, [int(lens2[b]) for b in ids],
+                                torch.cat([ks2[b] for b in ids]).contiguous(), torch.cat([vs2[b] for b in ids]).contiguous())
+        A.model.append(ids, [int(lens2[b]) for b in ids])
+        torch.cuda.synchronize()
+        table, hl, free = A.host_state()
+        assert table.tolist() == A.model.page_table() and hl.tolist() == lens2.tolist() and free.tolist() == A.model.free
+        _, _, d_table, d_lens = A.views()
+        import ctypes
+        hip = ctypes.CDLL("libamdhip64.so")
+        dev_table = torch.empty(cfg.batch * A.mpps, dtype=torch.int32, device=gu.DEV)
+        dev_lens = torch.empty(cfg.batch, dtype=torch.int32, device=gu.DEV)
+        assert hip.hipMemcpy(ctypes.c_void_p(dev_table.data_ptr()), ctypes.c_void_p(d_table),
+                             ctypes.c_size_t(dev_table.numel() * 4), 3) == 0
+        assert hip.hipMemcpy(ctypes.c_void_p(dev_lens.data_ptr()), ctypes.c_void_p(d_lens),
+                             ctypes.c_size_t(dev_lens.numel() * 4), 3) == 0
+        assert np.array_equal(dev_table.cpu().numpy().reshape(cfg.batch, A.mpps), table)
+        assert np.array_equal(dev_lens.cpu().numpy(), lens2)
+        expect = gu.oracle_attention(oracle, cfg, q2, ks2, vs2, table, lens2, A.n_pages)
+        out = gu.run_attention(cfg, A, q2, out_dtype=rb.RLHF_F32).cpu().numpy().astype(np.float64)
+        assert np.abs(out - expect).max() <= ATTN_TOL
+        assert not out[1].any()                                      # the empty sequence
+    finally:
+        A.close()
+
+
 def test_arena_with_a_hundred_thousand_sequences(gu):
     """Descriptor lists of 100,000 entries through the one-launch decode step,
     through the general path (edge tokens and whole pages in one call) and
