@@ -1037,6 +1037,40 @@ def test_calls_on_a_side_stream_give_the_same_results(gu):
         side = run(torch.cuda.Stream())
         for a, b in zip(base, side):
             assert torch.equal(a.view(torch.uint8), b.view(torch.uint8))
+
+        # four host threads at once, each on a stream of its own with buffers of its own:
+        # the compute entry points share no state that one caller could disturb for another
+        import threading
+        results, errors = {}, []
+
+        def worker(i):
+            try:
+                stream = torch.cuda.Stream()
+                ws = torch.empty(nws, dtype=torch.uint8, device=gu.DEV)
+                sw = torch.empty(sws, dtype=torch.uint8, device=gu.DEV)
+                out = torch.empty(cfg.batch, cfg.n_q_heads, cfg.head_dim, dtype=q.dtype, device=gu.DEV)
+                logp = torch.empty(cfg.n_positions, dtype=torch.float32, device=gu.DEV)
+                kl = torch.empty_like(logp)
+                draw = torch.empty(cfg.batch, dtype=torch.int32, device=gu.DEV)
+                for _ in range(10):
+                    rb.rlhf_decode_attention(params, q, k, v, table, dl, out, ws, stream=stream)
+                    rb.rlhf_token_logprobs_kl(actor, ref, tok, logp, kl, stream=stream)
+                    rb.rlhf_sample_tokens_split(actor[:cfg.batch], draw, 0.9, 77, sw, 3, stream=stream)
+                stream.synchronize()
+                results[i] = (out, logp, kl, draw)
+            except Exception as e:      # reported by the main thread
+                errors.append(e)
+
+        torch.cuda.synchronize()
+        threads = [threading.Thread(target=worker, args=(i,)) for i in range(4)]
+        for t in threads:
+            t.start()
+        for t in threads:
+            t.join()
+        assert not errors, errors
+        for i in range(4):
+            for a, b in zip(base, results[i]):
+                assert torch.equal(a.view(torch.uint8), b.view(torch.uint8)), i
     finally:
         A.close()
 
