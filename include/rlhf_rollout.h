@@ -28,7 +28,9 @@
  *     pass it a stream must be ordered with respect to each other on the
  *     device (one stream, or streams the caller orders with events): the
  *     arena's device mirrors and its append scratch change in that order.
- *     A workspace serves one call at a time in the same sense.
+ *     A workspace serves one call at a time in the same sense.  The compute
+ *     entry points keep no state between calls: several host threads may
+ *     call them at once, each with outputs and a workspace of its own.
  *   - The compute entry points (decode and prefill attention, log-prob/KL,
  *     the draws, the read probe) allocate nothing, issue no memset or copy and
  *     never synchronise: they may be recorded into a HIP graph on the stream
