@@ -238,7 +238,10 @@ int rlhf_decode_attention(const rlhf_attn_params *params, const void *q, const v
  *     logp_out[i] = log softmax(actor[i,:])[tokens[i]]
  *     kl_out[i]   = KL( softmax(actor[i,:]) || softmax(ref[i,:]) )   (nats, >= 0 up to rounding)
  * fp32 accumulation.  tokens[i] outside [0, vocab) marks padding: both
- * outputs are 0 for that position.
+ * outputs are 0 for that position.  Logits are finite or -infinity (a masked
+ * entry); a NaN logit gives NaN outputs for its row.  The outputs carry the
+ * fp32 rounding of the logits' own magnitude (about 1.2e-7 * max |logit|) on
+ * top of the error of the sums, which stays far below 1e-3.
  *
  *   actor_logits, ref_logits  dev [n_positions][row_stride_elems], logits_dtype
  *                             (RLHF_F32 or RLHF_BF16 or RLHF_F16); first `vocab` entries of a row used

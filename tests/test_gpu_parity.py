@@ -525,6 +525,31 @@ def test_logprobs_special_rows(gu, oracle):
     assert abs(logp[5]) <= 1e-6 and abs(logp[3]) <= 1e-3
 
 
+def test_logprobs_of_large_constant_rows_and_a_nan_row(gu, oracle):
+    """Logits of magnitude 1000 (the absolute error grows with the magnitude,
+    fp32 rounding of the logits themselves: 1e-3 still holds here); a NaN logit
+    marks its row."""
+    V = 3001
+    for tdt, big in ((torch.float32, 1000.0), (torch.bfloat16, 1024.0)):
+        actor = torch.zeros(5, V, dtype=torch.float32, device=gu.DEV)
+        actor[0] = -big                                     # constant, hugely negative: uniform
+        actor[1] = big                                      # constant, hugely positive
+        actor[2] = -big
+        actor[2, 11] = big                                  # one entry towers over the rest
+        actor[3] = torch.linspace(-1.0, 1.0, V, device=gu.DEV)
+        actor[3, 5] = float("nan")
+        actor[4] = torch.linspace(-5.0, 5.0, V, device=gu.DEV)
+        actor = actor.to(tdt)
+        ref = torch.zeros_like(actor)
+        tok = np.array([7, 8, 11, 9, 3000], dtype=np.int32)
+        logp, kl = gu.run_logprobs(actor, ref, tok)
+        el, _ = oracle.token_logprobs_kl(wl.to_storage(actor), wl.to_storage(ref), tok, rb.dtype_code(tdt))
+        assert np.isnan(logp[3]) and np.isnan(kl[3])
+        ok = [0, 1, 2, 4]
+        assert np.abs(logp[ok] - el[ok]).max() <= LOGP_TOL
+        assert abs(logp[0] + np.log(V)) <= LOGP_TOL and abs(logp[2]) <= LOGP_TOL
+
+
 @pytest.mark.parametrize("cfg_index", [2, 3, 5])
 def test_logprobs_full_size_sampled_rows(gu, oracle, cfg_index):
     """The benchmark's launch at the full shape; the oracle checks the first and
