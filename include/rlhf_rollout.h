@@ -358,8 +358,10 @@ int rlhf_sample_tokens_topk(const void *logits, int32_t *tokens_out, float *logp
  *   q          dev [cu_q[batch]][n_q_heads][head_dim], qkv_dtype, rows packed
  *              sequence after sequence
  *   cu_q       dev [batch+1] int32, non-decreasing, cu_q[0] = 0
- *   max_q_len  host: an upper bound on n_b.  It sizes the launch; rows of a
- *              sequence at or beyond max_q_len are NOT computed.
+ *   max_q_len  host: an upper bound on n_b.  It sizes the launch: a
+ *              sequence's rows at or beyond max_q_len may be left untouched
+ *              (those the launch's last block of positions still covers are
+ *              computed, the others are not).
  *   out        dev, same shape as q, out_dtype
  * A sequence with n_b = 0 is skipped; one with n_b > L_b (more query rows than
  * cached tokens) is skipped too and its rows of out are left untouched.

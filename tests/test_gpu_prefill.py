@@ -323,3 +323,29 @@ def test_lengths_above_max_seq_len_count_as_max_seq_len(gu, oracle):
         assert np.abs(outp.cpu().numpy().astype(np.float64) - expect).max() <= ATTN_TOL
     finally:
         A.close()
+
+
+def test_rows_past_max_q_len_are_correct_or_untouched(gu, oracle):
+    """max_q_len sizes the launch.  A sequence with more rows than that gets its
+    first max_q_len rows; each later row is either computed (the last block of
+    positions reaches it) or left as it was, never anything else."""
+    cfg = wl.small_variant(wl.config(3), batch=2, n_q_heads=4, n_kv_heads=2, len_lo=0, len_hi=1500)
+    lens = np.array([1500, 30], dtype=np.int32)
+    n_new = np.array([1400, 30], dtype=np.int32)
+    cu = np.concatenate([[0], np.cumsum(n_new)]).astype(np.int32)
+    _, ks, vs = wl.qkv(cfg, lens, device=gu.DEV)
+    q = wl.query_rows(cfg, int(cu[-1]), device=gu.DEV)
+    A = gu.FilledArena(cfg, lens, ks, vs)
+    try:
+        table, _, _ = A.host_state()
+        expect = _oracle(oracle, cfg, q, cu, ks, vs, table, lens, A.n_pages)
+        bound = 100
+        out = _run(gu, cfg, A, q, cu, bound, out_dtype=rb.RLHF_F32).cpu().numpy().astype(np.float64)
+        done = ~np.isnan(out).any(axis=(1, 2))
+        assert done[:bound].all() and done[cu[1]:].all()
+        assert not done[cu[1] - 1]                       # 1,400 rows are more than one block past 100
+        assert not np.isnan(out[done]).any()
+        assert (np.isnan(out[~done])).all()              # untouched rows hold the NaN fill in every element
+        assert np.abs(out[done] - expect[done]).max() <= ATTN_TOL
+    finally:
+        A.close()
