@@ -418,10 +418,10 @@ def test_attention_is_bit_identical_under_page_permutation(gu):
     assert torch.equal(outs[0].view(torch.int32), outs[1].view(torch.int32))
 
 
-@pytest.mark.parametrize("cfg_index", [2, 3, 4, 5])
-def test_attention_full_size_sampled_sequences(gu, oracle, cfg_index):
-    """The benchmark's launch configuration at the full shape; the oracle checks
-    a sample of whole sequences (shortest, longest, two seeded picks)."""
+@pytest.mark.parametrize("cfg_index", [1, 2, 3, 4, 5])
+def test_attention_full_size_every_element(gu, oracle, cfg_index):
+    """The benchmark's launch configuration at the full shape; the oracle
+    computes every sequence and the maximum error is taken over all elements."""
     cfg = wl.config(cfg_index)
     lens = wl.seq_lengths(cfg)
     _say(f"attention full cfg{cfg_index}: B={cfg.batch} tokens={int(lens.sum())}")
@@ -431,23 +431,26 @@ def test_attention_full_size_sampled_sequences(gu, oracle, cfg_index):
         table, hl, free = A.host_state()
         assert table.tolist() == A.model.page_table()
         assert hl.tolist() == lens.tolist() and free.tolist() == A.model.free
-        rng = np.random.default_rng(cfg.seed)
-        seqs = sorted({int(lens.argmin()), int(lens.argmax()), *rng.integers(0, cfg.batch, 2).tolist()})
-        expect = gu.oracle_attention(oracle, cfg, q, ks, vs, table, lens, A.n_pages, seqs=seqs)
+        expect = gu.oracle_attention(oracle, cfg, q, ks, vs, table, lens, A.n_pages)
+        assert expect.shape == (cfg.batch, cfg.n_q_heads, cfg.head_dim)
         out = gu.run_attention(cfg, A, q, out_dtype=rb.RLHF_F32, max_seq_len=cfg.len_hi)
         assert torch.isfinite(out).all()
-        err = np.abs(out[seqs].cpu().numpy().astype(np.float64) - expect).max()
+        err = np.abs(out.cpu().numpy().astype(np.float64) - expect).max()
         out16 = gu.run_attention(cfg, A, q, max_seq_len=cfg.len_hi)
-        err16 = np.abs(out16[seqs].float().cpu().numpy().astype(np.float64) - expect).max()
-        _say(f"  seqs {seqs}: max-abs err f32 out {err:.3e}, 16-bit out {err16:.3e}")
-        assert err <= ATTN_TOL and err16 <= ATTN_TOL
+        err16 = np.abs(out16.float().cpu().numpy().astype(np.float64) - expect).max()
+        _say(f"  all {expect.size} elements: max-abs err f32 out {err:.3e}, 16-bit out {err16:.3e}")
+        assert err <= ATTN_TOL
+        if cfg.len_lo >= 256 or cfg.kv_dtype == "f16":
+            assert err16 <= ATTN_TOL
+        else:   # caches of a few tokens: half an ulp of the 16-bit output itself
+            assert err16 <= ATTN_TOL + np.abs(expect).max() * 2.0 ** -8
         # property that holds at any size: every output inside the range of the values
-        b = seqs[0]
-        vmin = vs[b].float().amin(0)
-        vmax = vs[b].float().amax(0)
         G = cfg.n_q_heads // cfg.n_kv_heads
-        o = out[b].view(cfg.n_kv_heads, G, cfg.head_dim)
-        assert (o >= vmin[:, None, :] - 1e-5).all() and (o <= vmax[:, None, :] + 1e-5).all()
+        for b in (int(lens.argmin()), int(lens.argmax())):
+            vmin = vs[b].float().amin(0)
+            vmax = vs[b].float().amax(0)
+            o = out[b].view(cfg.n_kv_heads, G, cfg.head_dim)
+            assert (o >= vmin[:, None, :] - 1e-5).all() and (o <= vmax[:, None, :] + 1e-5).all()
     finally:
         A.close()
 
@@ -550,27 +553,45 @@ def test_logprobs_of_large_constant_rows_and_a_nan_row(gu, oracle):
         assert abs(logp[0] + np.log(V)) <= LOGP_TOL and abs(logp[2]) <= LOGP_TOL
 
 
-@pytest.mark.parametrize("cfg_index", [2, 3, 5])
-def test_logprobs_full_size_sampled_rows(gu, oracle, cfg_index):
-    """The benchmark's launch at the full shape; the oracle checks the first and
-    last rows and a seeded sample in between."""
+def _full_size_rows(cfg):
+    """Rows the oracle checks at the full shape: all of them, except for the
+    largest configuration (67 GB of logits), where it is the first 256, the last
+    256 and 1536 seeded rows in between."""
+    n = cfg.n_positions
+    if cfg.index != 5:
+        return np.arange(n)
+    rng = np.random.default_rng(cfg.seed)
+    mid = 256 + rng.choice(n - 512, size=1536, replace=False)
+    return np.sort(np.concatenate([np.arange(256), mid, np.arange(n - 256, n)]))
+
+
+@pytest.mark.parametrize("cfg_index", [1, 2, 3, 4, 5])
+def test_logprobs_full_size_every_row(gu, oracle, cfg_index):
+    """The benchmark's launch at the full shape.  The oracle scores every row of
+    configurations 1-4 (logits copied back in chunks of rows) and a fixed
+    2048-row sample of configuration 5; the maximum error is over all of them."""
     cfg = wl.config(cfg_index)
     n = cfg.n_positions
-    _say(f"logprob full cfg{cfg_index}: N={n} V={cfg.vocab} bytes={2 * n * cfg.vocab * 2 / 1e9:.1f} GB")
+    eb = 4 if cfg.logits_dtype == "f32" else 2
+    _say(f"logprob full cfg{cfg_index}: N={n} V={cfg.vocab} bytes={2 * n * cfg.vocab * eb / 1e9:.1f} GB")
     actor, ref = wl.logits(cfg, device=gu.DEV)
     tok = wl.tokens(cfg)
     logp, kl = gu.run_logprobs(actor, ref, tok)
     assert np.isfinite(logp).all() and np.isfinite(kl).all()
     assert (logp < 0).all() and (kl > -1e-5).all()
-    rng = np.random.default_rng(cfg.seed)
-    rows = np.unique(np.concatenate([np.arange(64), np.arange(n - 64, n), rng.integers(0, n, 128)]))
-    idx = torch.from_numpy(rows).to(gu.DEV)
-    el, ek = oracle.token_logprobs_kl(wl.to_storage(actor[idx]), wl.to_storage(ref[idx]), tok[rows],
-                                      wl.DTYPE_CODE[cfg.logits_dtype])
-    _say(f"  {rows.size} rows: max-abs err logp {np.abs(logp[rows] - el).max():.3e} "
-         f"kl {np.abs(kl[rows] - ek).max():.3e}")
-    assert np.abs(logp[rows] - el).max() <= LOGP_TOL
-    assert np.abs(kl[rows] - ek).max() <= LOGP_TOL
+    rows = _full_size_rows(cfg)
+    assert rows.size == (2048 if cfg_index == 5 else n) and np.unique(rows).size == rows.size
+    err_l = err_k = 0.0
+    for c0 in range(0, rows.size, 2048):
+        r = rows[c0:c0 + 2048]
+        idx = torch.from_numpy(r).to(gu.DEV)
+        el, ek = oracle.token_logprobs_kl(wl.to_storage(actor[idx]), wl.to_storage(ref[idx]), tok[r],
+                                          wl.DTYPE_CODE[cfg.logits_dtype])
+        err_l = max(err_l, np.abs(logp[r] - el).max())
+        err_k = max(err_k, np.abs(kl[r] - ek).max())
+    _say(f"  {rows.size} of {n} rows: max-abs err logp {err_l:.3e} kl {err_k:.3e}")
+    assert err_l <= LOGP_TOL
+    assert err_k <= LOGP_TOL
 
 
 @pytest.mark.parametrize("cfg_index,n", [(1, 64), (3, 48), (5, 16)])
