@@ -28,15 +28,17 @@
  *     pass it a stream must be ordered with respect to each other on the
  *     device (one stream, or streams the caller orders with events): the
  *     arena's device mirrors and its append scratch change in that order.
- *     A workspace serves one call at a time in the same sense.  The compute
- *     entry points keep no state between calls: several host threads may
- *     call them at once, each with outputs and a workspace of its own.
+ *     A workspace serves one call at a time in the same sense.  Several host
+ *     threads may call the compute entry points at once, each with outputs and
+ *     a workspace of its own; no call's result depends on an earlier call.
+ *     (rlhf_decode_attention keeps a few counters in device memory of the
+ *     library's own, one set per calling stream, zero between calls: see there.)
  *   - The compute entry points (decode and prefill attention, log-prob/KL,
  *     the draws, the read probe) allocate nothing, issue no memset or copy and
  *     never synchronise: they may be recorded into a HIP graph on the stream
  *     they are given and replayed; a replay reads the buffers' contents of
- *     that moment.  rlhf_kv_arena_append may not be recorded (its bookkeeping
- *     runs on the host at call time).
+ *     that moment.  rlhf_kv_arena_append and rlhf_kv_arena_free_seq may not
+ *     be recorded (their bookkeeping runs on the host at call time).
  *   - Compute entry points fail with RLHF_ERR_DEVICE when no HIP device is
  *     usable; there is no CPU fallback.
  *   - One kernel launch holds fewer than 2^32 lanes per grid dimension.  The
@@ -142,14 +144,43 @@ int rlhf_kv_arena_destroy(rlhf_kv_arena *arena);
  * (sum n_new * n_kv_heads) returns RLHF_ERR_UNSUPPORTED; in all three cases
  * nothing has changed.  The host
  * mirrors are updated before return; the device page table, lengths and K/V
- * pages are updated in stream order. */
+ * pages are updated in stream order.
+ *
+ * Waiting.  Each append and free_seq hands its changes to the device through
+ * one of four pinned command slots.  A call whose slot is still being read --
+ * that is, when the fourth-previous append/free_seq on this arena has not yet
+ * run on the device -- waits for that one (hipEventSynchronize) before it
+ * touches anything; otherwise the call does not synchronise.
+ *
+ * Device errors.  RLHF_ERR_DEVICE from that wait, or from a kernel launch the
+ * device refuses before any of the call's work was enqueued, leaves host and
+ * device mirrors unchanged (the host bookkeeping is taken back).  If an error
+ * strikes after part of the call was enqueued (a later launch of a multi-token
+ * append, or the event that guards the slot), the device will still apply what
+ * it was given: the call returns RLHF_ERR_DEVICE, the arena refuses append and
+ * free_seq from then on, and rlhf_kv_arena_reset (which rewrites both mirrors)
+ * makes it usable again.
+ *
+ * Neither append nor free_seq may be recorded into a HIP graph: their
+ * bookkeeping runs on the host at call time and the kernels read a pinned slot
+ * whose contents belong to that one call. */
 int rlhf_kv_arena_append(rlhf_kv_arena *arena, const int32_t *seq_ids /*host*/,
                          const int32_t *n_new /*host*/, int32_t n_seqs,
                          const void *k_new /*dev*/, const void *v_new /*dev*/, void *stream);
 
 /* Returns the pages of one sequence to the free-list tail; length becomes 0.
- * Device mirrors are updated in stream order. */
+ * Device mirrors are updated in stream order.  Waiting, device errors and graph
+ * capture: as for rlhf_kv_arena_append. */
 int rlhf_kv_arena_free_seq(rlhf_kv_arena *arena, int32_t seq_id, void *stream);
+
+/* Testing aid, not a step of the method: the next n_calls calls of
+ * rlhf_kv_arena_append / rlhf_kv_arena_free_seq on this arena that pass
+ * validation behave as if the device had refused their first kernel: they take
+ * their bookkeeping back through the same path a real refusal takes, enqueue
+ * nothing and return RLHF_ERR_DEVICE, so that "nothing has changed" can be
+ * checked (host mirrors, and device mirrors on a real arena) without a failing
+ * device.  Works on host-only arenas too.  n_calls = 0 switches it off. */
+int rlhf_kv_arena_fail_next_submissions(rlhf_kv_arena *arena, int32_t n_calls);
 
 /* Phase boundary: every page free again in initial_free_order, every length 0. */
 int rlhf_kv_arena_reset(rlhf_kv_arena *arena, void *stream);
@@ -210,6 +241,23 @@ int rlhf_kv_arena_gather(const rlhf_kv_arena *arena, int32_t seq_id, int32_t sta
  * q, k_arena, v_arena and out must be 16-byte aligned.  batch may not exceed
  * 8192 per call, nor batch * n_q_heads 2^26 - 4 (RLHF_ERR_UNSUPPORTED; split
  * larger batches).
+ *
+ * Launches.  The call is one kernel launch when it can be: the wavefront that
+ * completes a (sequence, head) unit merges the unit's split partials itself.
+ * That needs one arrival counter per unit, which cannot live in a workspace
+ * whose contents are undefined; the counters are device memory of the
+ * library's (zero when loaded, and every call leaves them zero), one set for
+ * each of the first 8 streams that call on a device, since calls on one stream
+ * never overlap.  The call falls back to two launches (split kernel, merge
+ * kernel; no state at all) while its stream is being captured into a graph, on
+ * further streams, above 32768 units per call (a unit is a (sequence, KV head)
+ * pair, or (sequence, query head) when the two counts are equal), and when the
+ * units are so few that one wavefront would have to merge dozens of partials.
+ * Both forms give the same results up to fp32 summation order; each is
+ * deterministic for given inputs, and neither depends on which physical pages
+ * a sequence owns.  A stream destroyed while a call on it is still running
+ * must not be replaced by a new stream that calls at once (the new one could
+ * be given the same handle and so the same counters).
  * ------------------------------------------------------------------------ */
 typedef struct {
     int32_t batch;

@@ -26,7 +26,8 @@ LIB_PATH = os.environ.get("RLHF_ROLLOUT_LIB") or os.path.join(os.path.dirname(os
 
 EXPORTS = [
     "rlhf_kv_arena_bytes_required", "rlhf_kv_arena_create", "rlhf_kv_arena_destroy",
-    "rlhf_kv_arena_append", "rlhf_kv_arena_free_seq", "rlhf_kv_arena_reset", "rlhf_kv_arena_stats",
+    "rlhf_kv_arena_append", "rlhf_kv_arena_free_seq", "rlhf_kv_arena_fail_next_submissions",
+    "rlhf_kv_arena_reset", "rlhf_kv_arena_stats",
     "rlhf_kv_arena_views", "rlhf_kv_arena_host_state", "rlhf_kv_arena_gather",
     "rlhf_decode_attention_workspace_bytes", "rlhf_decode_attention", "rlhf_token_logprobs_kl",
     "rlhf_token_logprobs_kl_rewards", "rlhf_sample_tokens", "rlhf_sample_tokens_workspace_bytes",
@@ -110,6 +111,7 @@ def lib() -> ctypes.CDLL:
         L.rlhf_kv_arena_destroy.argtypes = [vp]
         L.rlhf_kv_arena_append.argtypes = [vp, vp, vp, i32, vp, vp, vp]
         L.rlhf_kv_arena_free_seq.argtypes = [vp, i32, vp]
+        L.rlhf_kv_arena_fail_next_submissions.argtypes = [vp, i32]
         L.rlhf_kv_arena_reset.argtypes = [vp, vp]
         L.rlhf_kv_arena_stats.argtypes = [vp, P(ArenaStats)]
         L.rlhf_kv_arena_views.argtypes = [vp, P(vp), P(vp), P(vp), P(vp)]
@@ -225,6 +227,10 @@ def rlhf_kv_arena_append(arena: int, seq_ids: Sequence[int], n_new: Sequence[int
 
 def rlhf_kv_arena_free_seq(arena: int, seq_id: int, stream=None) -> None:
     _check(lib().rlhf_kv_arena_free_seq(arena, seq_id, _stream(stream)))
+
+
+def rlhf_kv_arena_fail_next_submissions(arena: int, n_calls: int) -> None:
+    _check(lib().rlhf_kv_arena_fail_next_submissions(arena, n_calls))
 
 
 def rlhf_kv_arena_reset(arena: int, stream=None) -> None:

@@ -271,6 +271,9 @@ struct rlhf_kv_arena {
     rlhf::CommandSlot ring[rlhf::kRingSlots];
     int next_slot = 0;
     rlhf::AppendPlan plan;
+    rlhf::FreePlan free_plan;
+    int fail_next = 0;  // testing aid: this many submissions are treated as refused by the device
+    bool broken = false;  // a device error struck after part of a call had been enqueued
 };
 
 namespace rlhf {
@@ -316,11 +319,12 @@ void release(rlhf_kv_arena *a)
     delete a;
 }
 
-// Takes the next command slot, waiting for its previous use if still in flight.
-int acquire_slot(rlhf_kv_arena *a, CommandSlot **out)
+// The next command slot, once its previous use (the call kRingSlots calls ago)
+// has left the device.  This is the one wait an append or a free can run into,
+// and it comes before anything is changed.  The slot is not taken yet.
+int wait_for_slot(rlhf_kv_arena *a, CommandSlot **out)
 {
     CommandSlot &s = a->ring[a->next_slot];
-    a->next_slot = (a->next_slot + 1) % kRingSlots;
     if (s.in_flight) {
         RLHF_HIP_TRY(hipEventSynchronize(s.done));
         s.in_flight = false;
@@ -329,15 +333,43 @@ int acquire_slot(rlhf_kv_arena *a, CommandSlot **out)
     return RLHF_OK;
 }
 
-int submit_slot(rlhf_kv_arena *a, CommandSlot *s, int work_items, hipStream_t stream)
+void take_slot(rlhf_kv_arena *a)
 {
+    a->next_slot = (a->next_slot + 1) % kRingSlots;
+}
+
+// After the kernel that reads the slot has been enqueued.  A failure here cannot
+// be undone (the kernel will run): the arena is marked broken.
+int mark_slot_in_flight(rlhf_kv_arena *a, CommandSlot *s, hipStream_t stream)
+{
+    const hipError_t e = hipEventRecord(s->done, stream);
+    if (e != hipSuccess) {
+        a->broken = true;
+        return fail(RLHF_ERR_DEVICE, "hipEventRecord failed after the update was enqueued: %s; the arena "
+                    "is unusable until rlhf_kv_arena_reset", hipGetErrorString(e));
+    }
+    s->in_flight = true;
+    return RLHF_OK;
+}
+
+// Launches the kernel that applies the slot's table / length changes.  When the
+// launch itself is refused nothing has been enqueued and the caller can undo its
+// bookkeeping.
+int submit_slot(rlhf_kv_arena *a, CommandSlot *s, int work_items, hipStream_t stream, bool *enqueued)
+{
+    *enqueued = false;
     const int blocks = std::min(64, std::max(1, (work_items + 255) / 256));
     hipLaunchKernelGGL(arena_apply_kernel, dim3(blocks), dim3(256), 0, stream, s->host, a->d_table,
                        a->d_lens, a->d_desc);
     RLHF_LAUNCH_CHECK("arena_apply_kernel");
-    RLHF_HIP_TRY(hipEventRecord(s->done, stream));
-    s->in_flight = true;
-    return RLHF_OK;
+    *enqueued = true;
+    return mark_slot_in_flight(a, s, stream);
+}
+
+int broken_arena()
+{
+    return fail(RLHF_ERR_DEVICE, "an earlier device error left this arena's device mirrors behind its host "
+                "bookkeeping: call rlhf_kv_arena_reset (or destroy it)");
 }
 
 int fill_i32(int32_t *p, int64_t n, int32_t value, hipStream_t stream)
@@ -462,19 +494,31 @@ extern "C" int rlhf_kv_arena_append(rlhf_kv_arena *arena, const int32_t *seq_ids
             return fail(RLHF_ERR_UNSUPPORTED, "append of %lld tokens x %d heads is too large for one launch: split the call",
                         (long long)total, arena->desc.n_kv_heads);
     }
+    if (arena->broken)
+        return broken_arena();
+    // The one step that can wait or fail before any kernel is launched comes first,
+    // so that a failure there finds the bookkeeping untouched.
+    CommandSlot *slot = nullptr;
+    if (!arena->host_only) {
+        const int rc = wait_for_slot(arena, &slot);
+        if (rc != RLHF_OK)
+            return rc;
+    }
     const ArenaBook::Result r = arena->book->append(seq_ids, n_new, n_seqs, &arena->plan);
     if (r == ArenaBook::kOom)
         return fail(RLHF_ERR_OOM, "arena has %d free pages, the call needs more", arena->book->pages_free());
     if (r != ArenaBook::kOk)
         return fail(RLHF_ERR_INVALID, "bad or repeated sequence id, negative count, or sequence past max_pages_per_seq");
+    if (arena->fail_next > 0) {  // as if the device had refused the call's first kernel
+        --arena->fail_next;
+        arena->book->undo_append(arena->plan);
+        return fail(RLHF_ERR_DEVICE, "simulated device failure: nothing has changed");
+    }
     if (arena->host_only || arena->plan.total_tokens == 0)
         return RLHF_OK;
 
     hipStream_t s = (hipStream_t)stream;
-    CommandSlot *slot = nullptr;
-    int rc = acquire_slot(arena, &slot);
-    if (rc != RLHF_OK)
-        return rc;
+    take_slot(arena);
     const AppendPlan &plan = arena->plan;
     int32_t *w = slot->host;
     int n_desc = 0;
@@ -522,14 +566,29 @@ extern "C" int rlhf_kv_arena_append(rlhf_kv_arena *arena, const int32_t *seq_ids
                            (const uint16_t *)v_new, (uint16_t *)arena->kv,
                            (uint16_t *)(arena->kv + arena->half_bytes), n_desc, (int)plan.new_pages.size(),
                            arena->desc.n_kv_heads, arena->desc.head_dim);
-        RLHF_LAUNCH_CHECK("kv_append_step_kernel");
-        RLHF_HIP_TRY(hipEventRecord(slot->done, s));
-        slot->in_flight = true;
-        return RLHF_OK;
+        if (hipGetLastError() != hipSuccess) {  // refused: nothing was enqueued
+            arena->book->undo_append(arena->plan);
+            return fail(RLHF_ERR_DEVICE, "launch of kv_append_step_kernel failed; nothing has changed");
+        }
+        return mark_slot_in_flight(arena, slot, s);
     }
-    rc = submit_slot(arena, slot, std::max<int>(kDescWords * n_desc, (int)plan.new_pages.size()), s);
-    if (rc != RLHF_OK)
+    bool enqueued = false;
+    int rc = submit_slot(arena, slot, std::max<int>(kDescWords * n_desc, (int)plan.new_pages.size()), s, &enqueued);
+    if (rc != RLHF_OK) {
+        if (!enqueued)
+            arena->book->undo_append(arena->plan);
         return rc;
+    }
+    // From here on the device mirrors carry the update: a refused launch of a copy
+    // kernel leaves rows unwritten that both mirrors count as present.
+    auto copy_launched = [&](const char *name) {
+        const hipError_t e = hipGetLastError();
+        if (e == hipSuccess)
+            return (int)RLHF_OK;
+        arena->broken = true;
+        return fail(RLHF_ERR_DEVICE, "launch of %s failed after the page table had been updated: %s; the "
+                    "arena is unusable until rlhf_kv_arena_reset", name, hipGetErrorString(e));
+    };
 
     if (whole_pages > 0) {
         hipLaunchKernelGGL(kv_scatter_pages_kernel, dim3((unsigned)((whole_pages * heads + 3) / 4)), dim3(256), 0, s,
@@ -537,7 +596,9 @@ extern "C" int rlhf_kv_arena_append(rlhf_kv_arena *arena, const int32_t *seq_ids
                            (uint16_t *)(arena->kv + arena->half_bytes), arena->d_table, arena->d_desc, n_desc,
                            whole_pages, arena->desc.n_kv_heads, arena->desc.head_dim,
                            arena->desc.max_pages_per_seq);
-        RLHF_LAUNCH_CHECK("kv_scatter_pages_kernel");
+        rc = copy_launched("kv_scatter_pages_kernel");
+        if (rc != RLHF_OK)
+            return rc;
     }
     if (edge_tokens > 0)
         hipLaunchKernelGGL(kv_scatter_kernel, dim3((unsigned)((edge_tokens * heads + 3) / 4)), dim3(256), 0, s,
@@ -545,8 +606,7 @@ extern "C" int rlhf_kv_arena_append(rlhf_kv_arena *arena, const int32_t *seq_ids
                            (uint16_t *)(arena->kv + arena->half_bytes), arena->d_table, arena->d_desc, n_desc,
                            edge_tokens, arena->desc.n_kv_heads, arena->desc.head_dim,
                            arena->desc.max_pages_per_seq);
-    RLHF_LAUNCH_CHECK("kv_scatter_kernel");
-    return RLHF_OK;
+    return copy_launched("kv_scatter_kernel");
 }
 
 extern "C" int rlhf_kv_arena_free_seq(rlhf_kv_arena *arena, int32_t seq_id, void *stream)
@@ -555,15 +615,25 @@ extern "C" int rlhf_kv_arena_free_seq(rlhf_kv_arena *arena, int32_t seq_id, void
         return fail(RLHF_ERR_INVALID, "NULL arena");
     if (seq_id < 0 || seq_id >= arena->desc.max_seqs)
         return fail(RLHF_ERR_INVALID, "sequence id %d out of range", seq_id);
+    if (arena->broken)
+        return broken_arena();
+    CommandSlot *slot = nullptr;
+    if (!arena->host_only) {
+        const int rc = wait_for_slot(arena, &slot);  // before anything changes
+        if (rc != RLHF_OK)
+            return rc;
+    }
     const int mpps = arena->desc.max_pages_per_seq;
     const int had = (arena->book->len(seq_id) + kPage - 1) / kPage;
-    arena->book->free_seq(seq_id);
+    arena->book->free_seq(seq_id, &arena->free_plan);
+    if (arena->fail_next > 0) {
+        --arena->fail_next;
+        arena->book->undo_free_seq(arena->free_plan);
+        return fail(RLHF_ERR_DEVICE, "simulated device failure: nothing has changed");
+    }
     if (arena->host_only)
         return RLHF_OK;
-    CommandSlot *slot = nullptr;
-    int rc = acquire_slot(arena, &slot);
-    if (rc != RLHF_OK)
-        return rc;
+    take_slot(arena);
     int32_t *w = slot->host;
     w[0] = 0;
     w[1] = had;
@@ -575,7 +645,19 @@ extern "C" int rlhf_kv_arena_free_seq(rlhf_kv_arena *arena, int32_t seq_id, void
     }
     w[4 + 2 * had] = seq_id;
     w[4 + 2 * had + 1] = 0;
-    return submit_slot(arena, slot, std::max(had, 1), (hipStream_t)stream);
+    bool enqueued = false;
+    const int rc = submit_slot(arena, slot, std::max(had, 1), (hipStream_t)stream, &enqueued);
+    if (rc != RLHF_OK && !enqueued)
+        arena->book->undo_free_seq(arena->free_plan);
+    return rc;
+}
+
+extern "C" int rlhf_kv_arena_fail_next_submissions(rlhf_kv_arena *arena, int32_t n_calls)
+{
+    if (!arena || n_calls < 0)
+        return fail(RLHF_ERR_INVALID, "NULL arena or negative count");
+    arena->fail_next = n_calls;
+    return RLHF_OK;
 }
 
 extern "C" int rlhf_kv_arena_reset(rlhf_kv_arena *arena, void *stream)
@@ -585,6 +667,7 @@ extern "C" int rlhf_kv_arena_reset(rlhf_kv_arena *arena, void *stream)
     arena->book->reset();
     if (arena->host_only)
         return RLHF_OK;
+    arena->broken = false;  // both mirrors are rewritten below
     hipStream_t s = (hipStream_t)stream;
     int rc = fill_i32(arena->d_table, (int64_t)arena->desc.max_seqs * arena->desc.max_pages_per_seq, -1, s);
     if (rc != RLHF_OK)

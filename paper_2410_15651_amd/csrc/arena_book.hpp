@@ -27,6 +27,14 @@ struct AppendPlan {
     std::vector<Seq> seqs;
     std::vector<NewPage> new_pages;
     int64_t total_tokens = 0;
+    int32_t peak_before = 0;  // peak_pages_in_use before the call, for undo_append
+};
+
+// What free_seq took away, for undo_free_seq.
+struct FreePlan {
+    int32_t seq = -1;
+    int32_t len = 0;
+    std::vector<int32_t> pages;  // in logical order
 };
 
 class ArenaBook {
@@ -89,6 +97,7 @@ public:
         plan->seqs.clear();
         plan->new_pages.clear();
         plan->total_tokens = 0;
+        plan->peak_before = peak_in_use_;
         for (int32_t i = 0; i < n_seqs; ++i) {
             const int32_t s = seq_ids[i], n = n_new[i];
             const int32_t start = lens_[s];
@@ -111,11 +120,33 @@ public:
         return kOk;
     }
 
-    Result free_seq(int32_t s)
+    // Takes back an append that has just succeeded (nothing else happened in
+    // between): every list and counter is as it was before the call.
+    void undo_append(const AppendPlan &plan)
+    {
+        for (auto it = plan.seqs.rbegin(); it != plan.seqs.rend(); ++it) {
+            lens_[it->seq] = it->start_len;
+            live_tokens_ -= it->n_new;
+            if (it->start_len == 0 && it->n_new > 0)
+                --live_seqs_;
+        }
+        for (auto it = plan.new_pages.rbegin(); it != plan.new_pages.rend(); ++it) {
+            table_[it->table_index] = -1;
+            free_.push_front(it->page);
+        }
+        peak_in_use_ = plan.peak_before;
+    }
+
+    Result free_seq(int32_t s, FreePlan *plan = nullptr)
     {
         if (s < 0 || s >= max_seqs_)
             return kInvalid;
         const int32_t have = (int32_t)pages_for(lens_[s]);
+        if (plan) {
+            plan->seq = s;
+            plan->len = lens_[s];
+            plan->pages.assign(table_.begin() + (size_t)s * mpps_, table_.begin() + (size_t)s * mpps_ + have);
+        }
         for (int32_t lp = 0; lp < have; ++lp) {
             free_.push_back(table_[(size_t)s * mpps_ + lp]);
             table_[(size_t)s * mpps_ + lp] = -1;
@@ -125,6 +156,19 @@ public:
         live_tokens_ -= lens_[s];
         lens_[s] = 0;
         return kOk;
+    }
+
+    // Takes back a free_seq that has just succeeded.
+    void undo_free_seq(const FreePlan &plan)
+    {
+        for (size_t lp = 0; lp < plan.pages.size(); ++lp) {
+            free_.pop_back();
+            table_[(size_t)plan.seq * mpps_ + lp] = plan.pages[lp];
+        }
+        lens_[plan.seq] = plan.len;
+        live_tokens_ += plan.len;
+        if (plan.len > 0)
+            ++live_seqs_;
     }
 
     int32_t max_seqs() const { return max_seqs_; }

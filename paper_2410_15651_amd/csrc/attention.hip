@@ -8,12 +8,28 @@
 // ranges, one per wavefront, for exactly as many wavefronts as the chip holds
 // at once.  A wavefront streams the pages of its range with an online softmax,
 // and whenever its range leaves a (sequence, head) unit -- or ends -- it writes
-// that unit's un-normalised partial (o, m, l).  A second kernel merges the
-// partials of each (sequence, query head) with log-sum-exp weights.  Every
-// wavefront gets the same number of pages whatever the mix of cache lengths,
-// pays its start-up latency once per call instead of once per chunk, and never
-// synchronises with another wavefront.  Ranges are defined on logical positions
-// only, so results do not depend on which physical pages a sequence owns.
+// that unit's un-normalised partial (o, m, l).  Every wavefront gets the same
+// number of pages whatever the mix of cache lengths, pays its start-up latency
+// once per call instead of once per chunk, and never waits for another
+// wavefront.  Ranges are defined on logical positions only, so results do not
+// depend on which physical pages a sequence owns.
+//
+// The partials of a unit are merged with log-sum-exp weights, in one of two
+// ways.  One launch: a wavefront whose range holds a whole unit normalises and
+// stores it at once; otherwise it stores its partial, waits until the stores
+// have landed and adds one to the unit's arrival counter, and the wavefront
+// that brings the counter to the number of ranges touching the unit -- known
+// from the page-count prefix alone -- sets the counter back to zero and merges
+// the unit's partials in range order, whoever it is, so the arithmetic does not
+// depend on the order of arrival.  Nobody waits.  Partials travel between
+// wavefronts through memory, around the per-XCD caches (see store_pair_device).  The counters are device
+// memory of the library's own (zero when the module is loaded, zero again after
+// every call), one set per stream that calls, because two calls running at once
+// must not share them.  Two launches: a second kernel with one wavefront per
+// (sequence, query head) does the merge; this needs no state at all and is what
+// runs while the stream is being captured into a graph, for streams beyond the
+// table, for calls with more units than a counter set holds, and for calls with
+// so few units that one wavefront would merge hundreds of partials.
 //
 // Partial slots need no bookkeeping: along the axis both the wavefront index w
 // and the unit index u only grow, and each new segment raises w + u by at least
@@ -69,6 +85,21 @@ constexpr int kMaxBatch = 8192;  // the per-workgroup page-count prefix lives in
 constexpr int kComputeUnits = 256;
 constexpr int kWavesPerCuMha = 8;
 constexpr int kWavesPerCuGqa = 4;
+
+// Arrival counters of the one-launch path: kStreamSets sets, one per calling
+// stream, each with room for kMaxFusedUnits (sequence, unit) pairs.
+constexpr int kStreamSets = 8;
+constexpr int kCounterSets = kStreamSets;
+constexpr int kMaxFusedUnits = 1 << 15;
+// The one-launch path is taken while a wavefront merges at most about this many
+// partials per unit on average (ranges / units); above that the merge kernel's
+// wavefront per query head is the better tool.
+constexpr int kFusedMaxAvgPartialsMha = 32;
+constexpr int kFusedMaxAvgPartialsGqa = 8;
+
+// Device memory owned by the library.  Host code never uses this name as an
+// address: the per-device address comes from hipGetSymbolAddress.
+static __device__ unsigned int g_arrivals[kCounterSets * kMaxFusedUnits];
 
 struct Shape {
     int batch, n_q_heads, n_kv_heads, group;
@@ -220,12 +251,99 @@ __device__ __forceinline__ int64_t range_begin(int64_t w, int64_t total, int n)
     return w * total / n;
 }
 
+// Wavefront that owns step s when `total` steps are cut into n ranges: the
+// largest w with w*total/n <= s (every range is non-empty).
+__device__ __forceinline__ int64_t range_owner(int64_t s, int64_t total, int64_t n)
+{
+    return ((s + 1) * n + total - 1) / total - 1;
+}
+
+// Two adjacent output elements (idx even), in fp32 or in the 16-bit type DT.
+template <int DT>
+__device__ __forceinline__ void store_pair(void *out, int64_t idx, float a, float b, bool as_f32)
+{
+    if (as_f32)
+        *(float2 *)((float *)out + idx) = make_float2(a, b);
+    else
+        *(uint32_t *)((uint16_t *)out + idx) = (uint32_t)pack16<DT>(a) | ((uint32_t)pack16<DT>(b) << 16);
+}
+
+// Log-sum-exp merge of a unit's partials, one partial at a time in range
+// order: (M, L) are the running reference exponent and sum; the caller then does
+// acc = fmaf(acc, alpha, e * v) for every element v of the partial's row.  Both
+// forms of the call (one launch, two launches) merge through this, in the same
+// order, so their outputs are bit-identical.
+__device__ __forceinline__ void merge_step(float &M, float &L, float m_i, float l_i, float &alpha, float &e)
+{
+    const float Mn = fmaxf(M, m_i);
+    alpha = fast_exp2(M - Mn);  // 0 for the first partial (M = -inf)
+    e = fast_exp2(m_i - Mn);
+    L = fmaf(L, alpha, e * l_i);
+    M = Mn;
+}
+
+// Partials cross between wavefronts on different XCDs, whose L2 caches are not
+// kept coherent with each other inside a kernel.  A device-wide release/acquire
+// fence would do, but it writes back and invalidates a whole L2, and with a
+// thousand wavefronts doing that the call takes twice as long (measured).  So
+// the partial rows themselves go around the caches instead: stored and loaded as
+// relaxed device-scope atomics (write-through stores, loads that do not trust a
+// cached line), 8 bytes at a time, and the only ordering needed is that a
+// wavefront's stores have been acknowledged before it counts itself in.
+__device__ __forceinline__ void store_pair_device(float *p, float a, float b)
+{
+    const uint64_t bits = (uint64_t)__float_as_uint(a) | ((uint64_t)__float_as_uint(b) << 32);
+    __hip_atomic_store((uint64_t *)p, bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ __forceinline__ float2 load_pair_device(const float *p)
+{
+    const uint64_t bits = __hip_atomic_load((const uint64_t *)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return make_float2(__uint_as_float((uint32_t)bits), __uint_as_float((uint32_t)(bits >> 32)));
+}
+
+// One arrival at a unit's counter, after this wavefront's partial (written with
+// store_pair_device by all lanes) has reached memory.  True for the wavefront
+// that completes the unit: it has put the counter back to zero and may read
+// every partial of the unit with load_pair_device.
+__device__ __forceinline__ bool arrive_last(unsigned int *counter, int count, int lane)
+{
+    __atomic_signal_fence(__ATOMIC_SEQ_CST);  // the compiler keeps the order below
+    __builtin_amdgcn_s_waitcnt(0);            // every store of this wavefront acknowledged
+    __atomic_signal_fence(__ATOMIC_SEQ_CST);
+    unsigned int old = 0;
+    if (lane == 0)
+        old = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    old = __builtin_amdgcn_readfirstlane(old);
+    __atomic_signal_fence(__ATOMIC_SEQ_CST);  // no load of a partial moves above the count
+    if (old != (unsigned int)(count - 1))
+        return false;
+    if (lane == 0)
+        __hip_atomic_store(counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return true;
+}
+
+// One-launch path: sequences without a cached token get zeros.  The launch's
+// wavefronts share the sequences out; w < n_waves for every wavefront launched.
+__device__ __forceinline__ void zero_empty_rows(const int *s_prefix, void *out, int out_f32, int batch,
+                                                int n_q_heads, int head_dim, int w, int n_waves, int lane)
+{
+    const int64_t n = (int64_t)n_q_heads * head_dim;  // elements of a sequence's output, even
+    for (int b = w; b < batch; b += n_waves) {
+        if (s_prefix[b + 1] != s_prefix[b])
+            continue;
+        for (int64_t i = 2 * lane; i < n; i += 128)
+            store_pair<RLHF_F16>(out, (int64_t)b * n + i, 0.f, 0.f, out_f32 != 0);  // 16-bit zero is type-independent
+    }
+}
+
 // ---- one query head per KV head: vector ALU ----------------------------------
 template <int DT, int D>
 __global__ __launch_bounds__(kThreads) void attn_stream_kernel(
     const uint16_t *__restrict__ q, const uint16_t *__restrict__ k_arena,
     const uint16_t *__restrict__ v_arena, const int32_t *__restrict__ page_table,
     const int32_t *__restrict__ seq_lens, int32_t *__restrict__ prefix_out, float *__restrict__ partials,
+    unsigned int *__restrict__ arrivals, void *__restrict__ out, int out_f32,
     int batch, int n_heads, int mpps, int max_len, int n_waves, float scale_log2)
 {
     constexpr int NL = D / 32;  // 16-byte loads per lane for one K (or V) block
@@ -233,7 +351,8 @@ __global__ __launch_bounds__(kThreads) void attn_stream_kernel(
     int *s_prefix = s_dyn;            // [batch + 1]
     int *s_scan = s_dyn + batch + 1;  // [256]
     const int total_pages = build_prefix(seq_lens, batch, max_len, s_prefix, s_scan);
-    if (blockIdx.x == 0)
+    const bool one_launch = arrivals != nullptr;
+    if (blockIdx.x == 0 && !one_launch)  // the merge kernel's copy of the prefix
         for (int i = threadIdx.x; i <= batch; i += kThreads)
             prefix_out[i] = s_prefix[i];
 
@@ -241,6 +360,8 @@ __global__ __launch_bounds__(kThreads) void attn_stream_kernel(
     const int w = __builtin_amdgcn_readfirstlane(blockIdx.x * kWgWaves + (threadIdx.x >> 6));
     const int64_t total = (int64_t)total_pages * n_heads;
     const int n_ranges = (int)min((int64_t)n_waves, total);  // never more wavefronts than steps
+    if (one_launch)
+        zero_empty_rows(s_prefix, out, out_f32, batch, n_heads, D, w, n_waves, lane);
     if (w >= n_ranges)
         return;
     const int64_t s0 = range_begin(w, total, n_ranges), s1 = range_begin(w + 1, total, n_ranges);
@@ -327,7 +448,11 @@ __global__ __launch_bounds__(kThreads) void attn_stream_kernel(
             acc1 = fmaf(pj[3], unpack_hi<DT>(vb[i].w), acc1);
         }
     };
-    // Writes the finished segment of unit (b, h) to slot w + unit and clears the state.
+    // Ends this wavefront's segment of unit (b, h) and clears the state.  Two
+    // launches: the partial goes to slot w + unit.  One launch: a segment that is
+    // the whole unit is normalised and stored; otherwise the partial is stored and
+    // counted, and the last of the unit's wavefronts to arrive merges them all.
+    int seg_page0 = cur.page;  // page of the unit at which this segment began
     auto flush = [&](const Cursor &c) {
         const float l_all = row16_sum(lsum);
         float o0 = acc0, o1 = acc1;
@@ -335,13 +460,53 @@ __global__ __launch_bounds__(kThreads) void attn_stream_kernel(
             o0 += __shfl_xor(o0, 32);
             o1 += __shfl_xor(o1, 32);
         }
-        float *dst = partials + ((int64_t)w + (int64_t)c.b * n_heads + c.h) * (D + 2);
-        if (lane < D / 2)
-            *(float2 *)(dst + 2 * lane) = make_float2(o0, o1);
-        if (lane == 0)
-            *(float2 *)(dst + D) = make_float2(m, l_all);
+        const int64_t unit = (int64_t)c.b * n_heads + c.h;
+        if (one_launch && seg_page0 == 0 && c.page == c.np - 1) {
+            const float inv = 1.0f / l_all;
+            if (lane < D / 2)
+                store_pair<DT>(out, unit * D + 2 * lane, o0 * inv, o1 * inv, out_f32 != 0);
+        } else {
+            float *dst = partials + ((int64_t)w + unit) * (D + 2);
+            if (lane < D / 2)
+                store_pair_device(dst + 2 * lane, o0, o1);
+            if (lane == 0)
+                store_pair_device(dst + D, m, l_all);
+            if (one_launch) {
+                const int64_t first = (int64_t)n_heads * s_prefix[c.b] + (int64_t)c.h * c.np;
+                const int64_t w_first = seg_page0 == 0 ? w : range_owner(first, total, n_ranges);
+                const int64_t w_last = c.page == c.np - 1 ? w : range_owner(first + c.np - 1, total, n_ranges);
+                const int count = (int)(w_last - w_first + 1);
+                if (arrive_last(arrivals + unit, count, lane)) {
+                    // partials w_first .. w_last of this unit, always in that order
+                    const float *src = partials + (w_first + unit) * (D + 2);
+                    const int dl = lane < D / 2 ? 2 * lane : 0;
+                    float M = -INFINITY, L = 0.f, a0 = 0.f, a1 = 0.f;
+                    for (int i0 = 0; i0 < count; i0 += 8) {
+                        float2 ml[8], ov[8];
+#pragma unroll
+                        for (int u = 0; u < 8; ++u) {  // eight rows in flight; past the end: the last row again, unused
+                            const float *row = src + (int64_t)min(i0 + u, count - 1) * (D + 2);
+                            ml[u] = load_pair_device(row + D);
+                            ov[u] = load_pair_device(row + dl);
+                        }
+#pragma unroll
+                        for (int u = 0; u < 8; ++u)
+                            if (i0 + u < count) {
+                                float alpha, e;
+                                merge_step(M, L, ml[u].x, ml[u].y, alpha, e);
+                                a0 = fmaf(a0, alpha, e * ov[u].x);
+                                a1 = fmaf(a1, alpha, e * ov[u].y);
+                            }
+                    }
+                    const float inv = 1.0f / L;
+                    if (lane < D / 2)
+                        store_pair<DT>(out, unit * D + 2 * lane, a0 * inv, a1 * inv, out_f32 != 0);
+                }
+            }
+        }
         m = -INFINITY;
         lsum = acc0 = acc1 = 0.f;
+        seg_page0 = 0;
     };
 
     // One page ahead: the next block's loads are in flight while the current one
@@ -381,6 +546,7 @@ __global__ __launch_bounds__(kThreads) void attn_stream_gqa_kernel(
     const uint16_t *__restrict__ q, const uint16_t *__restrict__ k_arena,
     const uint16_t *__restrict__ v_arena, const int32_t *__restrict__ page_table,
     const int32_t *__restrict__ seq_lens, int32_t *__restrict__ prefix_out, float *__restrict__ partials,
+    unsigned int *__restrict__ arrivals, void *__restrict__ out, int out_f32,
     int batch, int n_q_heads, int n_kv_heads, int mpps, int max_len, int n_waves, float scale_log2)
 {
     constexpr int NL = D / 32;
@@ -388,7 +554,8 @@ __global__ __launch_bounds__(kThreads) void attn_stream_gqa_kernel(
     int *s_prefix = s_dyn;
     int *s_scan = s_dyn + batch + 1;
     const int total_pages = build_prefix(seq_lens, batch, max_len, s_prefix, s_scan);
-    if (blockIdx.x == 0)
+    const bool one_launch = arrivals != nullptr;
+    if (blockIdx.x == 0 && !one_launch)
         for (int i = threadIdx.x; i <= batch; i += kThreads)
             prefix_out[i] = s_prefix[i];
 
@@ -400,6 +567,8 @@ __global__ __launch_bounds__(kThreads) void attn_stream_gqa_kernel(
     const int w = __builtin_amdgcn_readfirstlane(blockIdx.x * kWgWaves + (threadIdx.x >> 6));
     const int64_t total = (int64_t)total_pages * units;
     const int n_ranges = (int)min((int64_t)n_waves, total);  // never more wavefronts than steps
+    if (one_launch)
+        zero_empty_rows(s_prefix, out, out_f32, batch, n_q_heads, D, w, n_waves, lane);
     if (w >= n_ranges)
         return;
     const int64_t s0 = range_begin(w, total, n_ranges), s1 = range_begin(w + 1, total, n_ranges);
@@ -492,25 +661,101 @@ __global__ __launch_bounds__(kThreads) void attn_stream_gqa_kernel(
         }
     };
     // o[i][e][j] is row 4g+j of its tile, i.e. dim 32i + 2(4g+j) + e, for head c.
+    // Ends the segment as in attn_stream_kernel; a unit's partial is one row per
+    // query head of the unit, and the merging wavefront handles all heads at once
+    // (lane (g, c) keeps the 2 * 4 * NL dims it owns in the accumulator layout).
+    int seg_page0 = cur.page;
     auto flush = [&](const Cursor &cu) {
         float l_all = lsum + __shfl_xor(lsum, 16);
         l_all += __shfl_xor(l_all, 32);
-        if (c < n_heads_here) {
-            float *dst = partials +
-                         (((int64_t)w + (int64_t)cu.b * units + cu.h) * rows_per_unit + c) * (D + 2);
+        const int64_t unit = (int64_t)cu.b * units + cu.h;
+        const int hkv = cu.h / n_qb, qb = cu.h - hkv * n_qb;
+        const int64_t out_row = ((int64_t)cu.b * n_q_heads + hkv * group + qb * 16 + c) * D;
+        if (one_launch && seg_page0 == 0 && cu.page == cu.np - 1) {
+            if (c < n_heads_here) {
+                const float inv = 1.0f / l_all;
 #pragma unroll
-            for (int i = 0; i < NL; ++i)
+                for (int i = 0; i < NL; ++i)
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    *(float2 *)(dst + 32 * i + 2 * (4 * g + j)) = make_float2(o[i][0][j], o[i][1][j]);
-            if (g == 0)
-                *(float2 *)(dst + D) = make_float2(m, l_all);
+                    for (int j = 0; j < 4; ++j)
+                        store_pair<DT>(out, out_row + 32 * i + 2 * (4 * g + j), o[i][0][j] * inv,
+                                       o[i][1][j] * inv, out_f32 != 0);
+            }
+        } else {
+            if (c < n_heads_here) {
+                float *dst = partials + (((int64_t)w + unit) * rows_per_unit + c) * (D + 2);
+#pragma unroll
+                for (int i = 0; i < NL; ++i)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        store_pair_device(dst + 32 * i + 2 * (4 * g + j), o[i][0][j], o[i][1][j]);
+                if (g == 0)
+                    store_pair_device(dst + D, m, l_all);
+            }
+            if (one_launch) {
+                const int64_t first = (int64_t)units * s_prefix[cu.b] + (int64_t)cu.h * cu.np;
+                const int64_t w_first = seg_page0 == 0 ? w : range_owner(first, total, n_ranges);
+                const int64_t w_last = cu.page == cu.np - 1 ? w : range_owner(first + cu.np - 1, total, n_ranges);
+                const int count = (int)(w_last - w_first + 1);
+                if (arrive_last(arrivals + unit, count, lane) && c < n_heads_here) {
+                    // partials w_first .. w_last of this unit, always in that order, two per round trip
+                    const int64_t row_stride = (int64_t)rows_per_unit * (D + 2);
+                    const float *src = partials + ((w_first + unit) * rows_per_unit + c) * (D + 2);
+                    float M = -INFINITY, L = 0.f;
+                    float2 a[NL][4];
+#pragma unroll
+                    for (int i = 0; i < NL; ++i)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            a[i][j] = make_float2(0.f, 0.f);
+                    for (int i0 = 0; i0 < count; i0 += 2) {
+                        const float *r0 = src + (int64_t)i0 * row_stride;
+                        const float *r1 = src + (int64_t)min(i0 + 1, count - 1) * row_stride;
+                        const float2 ml0 = load_pair_device(r0 + D), ml1 = load_pair_device(r1 + D);
+                        float2 v0[NL][4], v1[NL][4];
+#pragma unroll
+                        for (int i = 0; i < NL; ++i)
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) {
+                                v0[i][j] = load_pair_device(r0 + 32 * i + 2 * (4 * g + j));
+                                v1[i][j] = load_pair_device(r1 + 32 * i + 2 * (4 * g + j));
+                            }
+                        float alpha, e;
+                        merge_step(M, L, ml0.x, ml0.y, alpha, e);
+#pragma unroll
+                        for (int i = 0; i < NL; ++i)
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) {
+                                a[i][j].x = fmaf(a[i][j].x, alpha, e * v0[i][j].x);
+                                a[i][j].y = fmaf(a[i][j].y, alpha, e * v0[i][j].y);
+                            }
+                        if (i0 + 1 < count) {  // otherwise r1 was the last row again, unused
+                            merge_step(M, L, ml1.x, ml1.y, alpha, e);
+#pragma unroll
+                            for (int i = 0; i < NL; ++i)
+#pragma unroll
+                                for (int j = 0; j < 4; ++j) {
+                                    a[i][j].x = fmaf(a[i][j].x, alpha, e * v1[i][j].x);
+                                    a[i][j].y = fmaf(a[i][j].y, alpha, e * v1[i][j].y);
+                                }
+                        }
+                    }
+                    const float inv = 1.0f / L;
+#pragma unroll
+                    for (int i = 0; i < NL; ++i)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            store_pair<DT>(out, out_row + 32 * i + 2 * (4 * g + j), a[i][j].x * inv,
+                                           a[i][j].y * inv, out_f32 != 0);
+                }
+            }
         }
         m = -INFINITY;
         lsum = 0.f;
 #pragma unroll
         for (int i = 0; i < NL; ++i)
             o[i][0] = o[i][1] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        seg_page0 = 0;
     };
 
     // one page ahead, last step peeled (see attn_stream_kernel)
@@ -575,51 +820,33 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(
         o[k] = 0.f;
     if (np > 0) {
         const int64_t first = (int64_t)units * prefix[b] + (int64_t)h * np, last = first + np - 1;
-        // wavefront that owns step s: the largest w with w*total/n <= s, where n is
-        // the number of ranges the stream kernel used (every range is non-empty)
-        const int64_t n = min((int64_t)n_waves, total);
-        const int64_t w_first = ((first + 1) * n + total - 1) / total - 1;
-        const int64_t w_last = ((last + 1) * n + total - 1) / total - 1;
+        const int64_t n = min((int64_t)n_waves, total);  // ranges the stream kernel used
+        const int64_t w_first = range_owner(first, total, n), w_last = range_owner(last, total, n);
         const int count = (int)(w_last - w_first + 1);
         const int64_t row_stride = (int64_t)rows_per_unit * (D + 2);
         const float *base = partials + ((w_first + (int64_t)b * units + h) * rows_per_unit + col) * (D + 2);
-        // pass 1: the largest exponent; lanes take one segment each
+        // partials w_first .. w_last in that order, four rows in flight
         float M = -INFINITY;
-        for (int i = lane; i < count; i += 64)
-            M = fmaxf(M, base[i * row_stride + D]);
-        M = wave_max(M);
-        // pass 2: weights per lane, then the weighted rows with several loads in flight
-        for (int i0 = 0; i0 < count; i0 += 64) {
-            const int i = i0 + lane;
-            float e = 0.f, le = 0.f;
-            if (i < count) {
-                e = fast_exp2(base[i * row_stride + D] - M);
-                le = base[i * row_stride + D + 1] * e;
-            }
-            l += wave_sum(le);
-            const int chunk = min(64, count - i0);
-            int j = 0;
-            for (; j + 4 <= chunk; j += 4) {
-                float v[4][PER], ej[4];
+        for (int i0 = 0; i0 < count; i0 += 4) {
+            float2 ml[4];
+            float v[4][PER];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    ej[u] = __shfl(e, j + u);
-#pragma unroll
-                    for (int k = 0; k < PER; ++k)
-                        v[u][k] = base[(int64_t)(i0 + j + u) * row_stride + lane + 64 * k];
-                }
-#pragma unroll
-                for (int u = 0; u < 4; ++u)
-#pragma unroll
-                    for (int k = 0; k < PER; ++k)
-                        o[k] = fmaf(v[u][k], ej[u], o[k]);
-            }
-            for (; j < chunk; ++j) {
-                const float ej = __shfl(e, j);
+            for (int u = 0; u < 4; ++u) {  // past the end: the last row again, unused
+                const float *r = base + (int64_t)min(i0 + u, count - 1) * row_stride;
+                ml[u] = *(const float2 *)(r + D);
 #pragma unroll
                 for (int k = 0; k < PER; ++k)
-                    o[k] = fmaf(base[(int64_t)(i0 + j) * row_stride + lane + 64 * k], ej, o[k]);
+                    v[u][k] = r[lane + 64 * k];
             }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (i0 + u < count) {
+                    float alpha, e;
+                    merge_step(M, l, ml[u].x, ml[u].y, alpha, e);
+#pragma unroll
+                    for (int k = 0; k < PER; ++k)
+                        o[k] = fmaf(o[k], alpha, e * v[u][k]);
+                }
         }
     }
     const float inv = np > 0 ? 1.0f / l : 0.f;
@@ -661,41 +888,62 @@ int check_params(const rlhf_attn_params *p)
     return RLHF_OK;
 }
 
-// Wavefronts the device can hold at once for a kernel, capped by the sizing
-// bound.  The occupancy query is remembered per (device, kernel, LDS bytes).
-struct ResidentEntry {
-    int device;
-    const void *kernel;
-    size_t lds;
-    int waves;
+// Per-device addresses of the library's own device memory and the table that
+// gives each calling stream a counter set of its own.  Filled on the first call
+// on a device, with that device current.
+constexpr int kMaxDevices = 64;
+struct DeviceState {
+    bool ready = false;
+    int compute_units = 0;
+    unsigned int *arrivals = nullptr;   // g_arrivals on this device
+    int n_streams = 0;
+    hipStream_t streams[kStreamSets] = {};
 };
-std::mutex g_resident_mutex;
-std::vector<ResidentEntry> g_resident;
+std::mutex g_device_mutex;
+DeviceState g_devices[kMaxDevices];
 
-template <typename Kernel>
-int resident_waves(Kernel kernel, size_t lds_bytes, int bound, int *out)
+int device_state(DeviceState **out)
 {
     int dev = 0;
     RLHF_HIP_TRY(hipGetDevice(&dev));
-    const void *key = reinterpret_cast<const void *>(kernel);
-    {
-        std::lock_guard<std::mutex> lock(g_resident_mutex);
-        for (const auto &e : g_resident)
-            if (e.device == dev && e.kernel == key && e.lds == lds_bytes) {
-                *out = std::min(e.waves, bound);
-                return RLHF_OK;
-            }
+    if (dev < 0 || dev >= kMaxDevices)
+        return fail(RLHF_ERR_UNSUPPORTED, "device index %d", dev);
+    std::lock_guard<std::mutex> lock(g_device_mutex);
+    DeviceState &d = g_devices[dev];
+    if (!d.ready) {
+        RLHF_HIP_TRY(hipDeviceGetAttribute(&d.compute_units, hipDeviceAttributeMultiprocessorCount, dev));
+        RLHF_HIP_TRY(hipGetSymbolAddress((void **)&d.arrivals, HIP_SYMBOL(g_arrivals)));
+        d.ready = true;
     }
-    int cus = 0, blocks = 0;
-    RLHF_HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
-    RLHF_HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, kernel, kThreads, lds_bytes));
-    const int waves = (int)std::min<int64_t>((int64_t)cus * std::max(blocks, 1) * kWgWaves, 1 << 20);
-    {
-        std::lock_guard<std::mutex> lock(g_resident_mutex);
-        g_resident.push_back({dev, key, lds_bytes, waves});
-    }
-    *out = std::min(waves, bound);
+    *out = &d;
     return RLHF_OK;
+}
+
+// Counter set of a stream on this device, or -1 when the table is full.  Calls
+// on one stream run one after the other, so they can share a set; a stream keeps
+// its set for the life of the process.
+int counter_set_of(DeviceState *d, hipStream_t s)
+{
+    std::lock_guard<std::mutex> lock(g_device_mutex);
+    for (int i = 0; i < d->n_streams; ++i)
+        if (d->streams[i] == s)
+            return i;
+    if (d->n_streams == kStreamSets)
+        return -1;
+    d->streams[d->n_streams] = s;
+    return d->n_streams++;
+}
+
+// Whether kernels launched on s now are being recorded rather than run.  A
+// failing query counts as "yes": the stateless path is always right.
+bool being_captured(hipStream_t s)
+{
+    hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(s, &st) != hipSuccess) {
+        (void)hipGetLastError();
+        return true;
+    }
+    return st != hipStreamCaptureStatusNone;
 }
 
 template <int DT, int D>
@@ -704,29 +952,49 @@ int launch(const rlhf_attn_params &p, const Shape &sh, const void *q, const void
            void *workspace, hipStream_t s)
 {
     const float scale = p.softmax_scale != 0.f ? p.softmax_scale : 1.0f / sqrtf((float)D);
+    const size_t lds = ((size_t)p.batch + 1 + kThreads) * sizeof(int);
+    const int64_t n_units = (int64_t)p.batch * sh.units_per_seq;
+    const int waves_per_cu = sh.group == 1 ? kWavesPerCuMha : kWavesPerCuGqa;
+
+    // One launch or two (see the top of the file).
+    unsigned int *arrivals = nullptr;
+    int n_waves = sh.n_waves;
+    const bool capturing = being_captured(s);
+    if (!capturing) {
+        DeviceState *d = nullptr;
+        const int rc = device_state(&d);
+        if (rc != RLHF_OK)
+            return rc;
+        n_waves = std::min(sh.n_waves, std::max(d->compute_units, 1) * waves_per_cu);
+        // ranges the kernel will cut the axis into, at most: wavefronts, or page steps if fewer
+        const int64_t ranges = std::min<int64_t>(n_waves, n_units * ((sh.max_len + kPage - 1) / kPage));
+        const int avg_cap = sh.group == 1 ? kFusedMaxAvgPartialsMha : kFusedMaxAvgPartialsGqa;
+        if (n_units <= kMaxFusedUnits && ranges <= avg_cap * n_units) {
+            const int set = counter_set_of(d, s);
+            if (set >= 0)
+                arrivals = d->arrivals + (size_t)set * kMaxFusedUnits;
+        }
+    }
     int32_t *prefix = (int32_t *)workspace;
     float *partials = (float *)((char *)workspace + prefix_bytes(sh));
-    const size_t lds = ((size_t)p.batch + 1 + kThreads) * sizeof(int);
-    int n_waves = 0, rc;
+    const int out_f32 = p.out_dtype == RLHF_F32;
+
     if (sh.group == 1) {
-        rc = resident_waves(attn_stream_kernel<DT, D>, lds, sh.n_waves, &n_waves);
-        if (rc != RLHF_OK)
-            return rc;
         hipLaunchKernelGGL((attn_stream_kernel<DT, D>), dim3(n_waves / kWgWaves), dim3(kThreads), lds, s,
                            (const uint16_t *)q, (const uint16_t *)k_arena, (const uint16_t *)v_arena,
-                           page_table, seq_lens, prefix, partials, p.batch, p.n_q_heads, p.max_pages_per_seq,
-                           sh.max_len, n_waves, scale * kLog2e);
+                           page_table, seq_lens, prefix, partials, arrivals, out, out_f32, p.batch,
+                           p.n_q_heads, p.max_pages_per_seq, sh.max_len, n_waves, scale * kLog2e);
         RLHF_LAUNCH_CHECK("attn_stream_kernel");
     } else {
-        rc = resident_waves(attn_stream_gqa_kernel<DT, D>, lds, sh.n_waves, &n_waves);
-        if (rc != RLHF_OK)
-            return rc;
         hipLaunchKernelGGL((attn_stream_gqa_kernel<DT, D>), dim3(n_waves / kWgWaves), dim3(kThreads), lds, s,
                            (const uint16_t *)q, (const uint16_t *)k_arena, (const uint16_t *)v_arena,
-                           page_table, seq_lens, prefix, partials, p.batch, p.n_q_heads, p.n_kv_heads,
-                           p.max_pages_per_seq, sh.max_len, n_waves, scale * kLog2e);
+                           page_table, seq_lens, prefix, partials, arrivals, out, out_f32, p.batch,
+                           p.n_q_heads, p.n_kv_heads, p.max_pages_per_seq, sh.max_len, n_waves,
+                           scale * kLog2e);
         RLHF_LAUNCH_CHECK("attn_stream_gqa_kernel");
     }
+    if (arrivals != nullptr)
+        return RLHF_OK;
     const int64_t rows = (int64_t)p.batch * p.n_q_heads;
     const dim3 mgrid((unsigned)((rows + 3) / 4));
     if (p.out_dtype == RLHF_F32)
@@ -737,6 +1005,40 @@ int launch(const rlhf_attn_params &p, const Shape &sh, const void *q, const void
                            p.n_q_heads, p.n_kv_heads, n_waves);
     RLHF_LAUNCH_CHECK("attn_merge_kernel");
     return RLHF_OK;
+}
+
+size_t workspace_need(const rlhf_attn_params &p, const Shape &sh)
+{
+    return prefix_bytes(sh) + partial_rows(sh) * (p.head_dim + 2) * sizeof(float);
+}
+
+int decode_attention(const rlhf_attn_params *params, const void *q, const void *k_arena, const void *v_arena,
+                     const int32_t *page_table, const int32_t *seq_lens, void *out, void *workspace,
+                     size_t workspace_bytes_given, void *stream)
+{
+    int rc = check_params(params);
+    if (rc != RLHF_OK)
+        return rc;
+    const rlhf_attn_params &p = *params;
+    if (p.batch == 0)
+        return RLHF_OK;
+    if (!q || !k_arena || !v_arena || !page_table || !seq_lens || !out || !workspace)
+        return fail(RLHF_ERR_INVALID, "NULL pointer");
+    if (((uintptr_t)q | (uintptr_t)k_arena | (uintptr_t)v_arena | (uintptr_t)out | (uintptr_t)workspace) % 16)
+        return fail(RLHF_ERR_INVALID, "q, k_arena, v_arena, out and workspace must be 16-byte aligned");
+    const Shape sh = make_shape(p);
+    const size_t need = workspace_need(p, sh);
+    if (workspace_bytes_given < need)
+        return fail(RLHF_ERR_INVALID, "workspace holds %zu bytes, %zu needed", workspace_bytes_given, need);
+    hipStream_t s = (hipStream_t)stream;
+    if (p.qkv_dtype == RLHF_BF16) {
+        if (p.head_dim == 128)
+            return launch<RLHF_BF16, 128>(p, sh, q, k_arena, v_arena, page_table, seq_lens, out, workspace, s);
+        return launch<RLHF_BF16, 64>(p, sh, q, k_arena, v_arena, page_table, seq_lens, out, workspace, s);
+    }
+    if (p.head_dim == 128)
+        return launch<RLHF_F16, 128>(p, sh, q, k_arena, v_arena, page_table, seq_lens, out, workspace, s);
+    return launch<RLHF_F16, 64>(p, sh, q, k_arena, v_arena, page_table, seq_lens, out, workspace, s);
 }
 
 }  // namespace
@@ -751,8 +1053,7 @@ extern "C" int rlhf_decode_attention_workspace_bytes(const rlhf_attn_params *par
     int rc = check_params(params);
     if (rc != RLHF_OK)
         return rc;
-    const Shape sh = make_shape(*params);
-    *out_bytes = prefix_bytes(sh) + partial_rows(sh) * (params->head_dim + 2) * sizeof(float);
+    *out_bytes = workspace_need(*params, make_shape(*params));
     return RLHF_OK;
 }
 
@@ -760,27 +1061,6 @@ extern "C" int rlhf_decode_attention(const rlhf_attn_params *params, const void 
                                      const void *v_arena, const int32_t *page_table, const int32_t *seq_lens,
                                      void *out, void *workspace, size_t workspace_bytes_given, void *stream)
 {
-    int rc = check_params(params);
-    if (rc != RLHF_OK)
-        return rc;
-    const rlhf_attn_params &p = *params;
-    if (p.batch == 0)
-        return RLHF_OK;
-    if (!q || !k_arena || !v_arena || !page_table || !seq_lens || !out || !workspace)
-        return fail(RLHF_ERR_INVALID, "NULL pointer");
-    if (((uintptr_t)q | (uintptr_t)k_arena | (uintptr_t)v_arena | (uintptr_t)out | (uintptr_t)workspace) % 16)
-        return fail(RLHF_ERR_INVALID, "q, k_arena, v_arena, out and workspace must be 16-byte aligned");
-    const Shape sh = make_shape(p);
-    const size_t need = prefix_bytes(sh) + partial_rows(sh) * (p.head_dim + 2) * sizeof(float);
-    if (workspace_bytes_given < need)
-        return fail(RLHF_ERR_INVALID, "workspace holds %zu bytes, %zu needed", workspace_bytes_given, need);
-    hipStream_t s = (hipStream_t)stream;
-    if (p.qkv_dtype == RLHF_BF16) {
-        if (p.head_dim == 128)
-            return launch<RLHF_BF16, 128>(p, sh, q, k_arena, v_arena, page_table, seq_lens, out, workspace, s);
-        return launch<RLHF_BF16, 64>(p, sh, q, k_arena, v_arena, page_table, seq_lens, out, workspace, s);
-    }
-    if (p.head_dim == 128)
-        return launch<RLHF_F16, 128>(p, sh, q, k_arena, v_arena, page_table, seq_lens, out, workspace, s);
-    return launch<RLHF_F16, 64>(p, sh, q, k_arena, v_arena, page_table, seq_lens, out, workspace, s);
+    return decode_attention(params, q, k_arena, v_arena, page_table, seq_lens, out, workspace,
+                            workspace_bytes_given, stream);
 }

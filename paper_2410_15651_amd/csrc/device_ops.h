@@ -67,6 +67,11 @@ __device__ __forceinline__ uint16_t pack16(float x)
         u += 0x7fffu + ((u >> 16) & 1u);
         return (uint16_t)(u >> 16);
     } else {
+        // The value is rounded to fp32 first and to fp16 second, always: the empty
+        // statement keeps the compiler from folding the caller's last multiply into a
+        // mixed-precision instruction that rounds once (the two can differ in the last
+        // bit, and one call site may get the fold while another does not).
+        asm volatile("" : "+v"(x));
         _Float16 h = (_Float16)x;  // v_cvt_f16_f32, RNE
         return __builtin_bit_cast(uint16_t, h);
     }

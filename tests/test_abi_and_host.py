@@ -110,6 +110,45 @@ def test_failed_appends_change_nothing():
         rb.rlhf_kv_arena_destroy(h)
 
 
+def test_a_refused_submission_takes_the_bookkeeping_back():
+    """A device error before anything was enqueued must leave the arena as it was.
+    The testing aid makes the next calls take exactly the path a refused kernel
+    launch takes (bookkeeping done, then undone); the state is compared with the
+    Python model, which never saw the failed calls."""
+    order = [4, 2, 5, 0, 1, 3, 7, 6]
+    h, cfg = _host_arena(n_pages=8, max_pages_per_seq=4, initial_free_order=order)
+    m = ArenaModel(3, 2, 64, P, 8, 4, initial_free_order=order)
+    try:
+        rb.rlhf_kv_arena_append(h, [1, 0], [17, 1])
+        m.append([1, 0], [17, 1])
+        _compare(h, cfg, m)
+        rb.rlhf_kv_arena_fail_next_submissions(h, 3)
+        # new pages for two sequences, a first token for a third: pages, lengths, live_seqs, peak all move
+        with pytest.raises(rb.RlhfError) as e:
+            rb.rlhf_kv_arena_append(h, [0, 2, 1], [31, 5, 20])
+        assert e.value.status == rb.RLHF_ERR_DEVICE
+        _compare(h, cfg, m)
+        with pytest.raises(rb.RlhfError) as e:
+            rb.rlhf_kv_arena_free_seq(h, 1)
+        assert e.value.status == rb.RLHF_ERR_DEVICE
+        _compare(h, cfg, m)
+        with pytest.raises(rb.RlhfError):                     # a call that fails validation does not use one up
+            rb.rlhf_kv_arena_append(h, [0], [1000])
+        with pytest.raises(rb.RlhfError) as e:
+            rb.rlhf_kv_arena_free_seq(h, 2)                   # an empty sequence
+        assert e.value.status == rb.RLHF_ERR_DEVICE
+        _compare(h, cfg, m)
+        # the aid has run out: the same calls now go through, from exactly the state the model is in
+        rb.rlhf_kv_arena_append(h, [0, 2, 1], [31, 5, 20])
+        m.append([0, 2, 1], [31, 5, 20])
+        _compare(h, cfg, m)
+        rb.rlhf_kv_arena_free_seq(h, 1)
+        m.free_seq(1)
+        _compare(h, cfg, m)
+    finally:
+        rb.rlhf_kv_arena_destroy(h)
+
+
 def test_create_rejects_bad_descriptions():
     bad = [
         dict(page_tokens=8), dict(head_dim=96), dict(kv_dtype=rb.RLHF_F32), dict(n_pages=0),

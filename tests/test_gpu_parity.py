@@ -24,6 +24,11 @@ def gu():
     return gpu_util
 
 
+def _bits_differ(a, b):
+    """Number of bytes in which two tensors differ (0: bit-identical)."""
+    return int((a.contiguous().view(torch.uint8) != b.contiguous().view(torch.uint8)).sum())
+
+
 def _say(msg):
     print(msg, flush=True)
 
@@ -110,6 +115,78 @@ def test_arena_append_gather_and_layout_bit_exact(gu, cfg_index, batch):
         torch.cuda.synchronize()
         assert torch.equal(ko.view(torch.int16), ks[-1][:5].view(torch.int16))
         assert torch.equal(vo.view(torch.int16), vs[-1][:5].view(torch.int16))
+    finally:
+        A.close()
+
+
+def _device_mirrors(gu, A):
+    """Device page table and lengths of a filled arena, copied back."""
+    import ctypes
+    _, _, d_table, d_lens = A.views()
+    table = torch.empty(A.cfg.batch * A.mpps, dtype=torch.int32, device=gu.DEV)
+    lens = torch.empty(A.cfg.batch, dtype=torch.int32, device=gu.DEV)
+    hip = ctypes.CDLL("libamdhip64.so")
+    torch.cuda.synchronize()
+    assert hip.hipMemcpy(ctypes.c_void_p(table.data_ptr()), ctypes.c_void_p(d_table),
+                         ctypes.c_size_t(table.numel() * 4), 3) == 0
+    assert hip.hipMemcpy(ctypes.c_void_p(lens.data_ptr()), ctypes.c_void_p(d_lens),
+                         ctypes.c_size_t(lens.numel() * 4), 3) == 0
+    return table.cpu().numpy().reshape(A.cfg.batch, A.mpps).tolist(), lens.cpu().numpy().tolist()
+
+
+def test_arena_refused_submission_leaves_host_and_device_mirrors_alone(gu):
+    """A device error before any of a call's work is enqueued: the call returns
+    RLHF_ERR_DEVICE and host and device bookkeeping are what they were, so the
+    same call then goes through and the read-back is exact.  The refusal is the
+    library's testing aid, which takes the path a refused first launch takes.
+    Twelve appends in a row without a synchronisation also run through the four
+    command slots three times (a call waits for the fourth-previous one)."""
+    cfg = wl.small_variant(wl.config(4), batch=5, n_q_heads=4, n_kv_heads=4, len_lo=20, len_hi=90)
+    lens = wl.seq_lengths(cfg)
+    q, ks, vs = wl.qkv(cfg, lens, device=gu.DEV)
+    A = gu.FilledArena(cfg, lens, ks, vs, slack_pages=12, extra_tokens=40)
+    try:
+        before = ([x.tolist() for x in A.host_state()], rb.rlhf_kv_arena_stats(A.handle), _device_mirrors(gu, A))
+        extra_k = [torch.randn(30, cfg.n_kv_heads, cfg.head_dim, device=gu.DEV).to(ks[0].dtype) for _ in range(cfg.batch)]
+        extra_v = [torch.randn(30, cfg.n_kv_heads, cfg.head_dim, device=gu.DEV).to(ks[0].dtype) for _ in range(cfg.batch)]
+        ids = [3, 0, 4]
+        k_new = torch.cat([extra_k[b][:n] for b, n in zip(ids, (30, 1, 17))]).contiguous()
+        v_new = torch.cat([extra_v[b][:n] for b, n in zip(ids, (30, 1, 17))]).contiguous()
+        rb.rlhf_kv_arena_fail_next_submissions(A.handle, 2)
+        with pytest.raises(rb.RlhfError) as e:
+            rb.rlhf_kv_arena_append(A.handle, ids, [30, 1, 17], k_new, v_new)
+        assert e.value.status == rb.RLHF_ERR_DEVICE
+        with pytest.raises(rb.RlhfError) as e:
+            rb.rlhf_kv_arena_free_seq(A.handle, 1)
+        assert e.value.status == rb.RLHF_ERR_DEVICE
+        after = ([x.tolist() for x in A.host_state()], rb.rlhf_kv_arena_stats(A.handle), _device_mirrors(gu, A))
+        assert after == before
+        # the same calls now succeed, from the unchanged state
+        rb.rlhf_kv_arena_append(A.handle, ids, [30, 1, 17], k_new, v_new)
+        A.model.append(ids, [30, 1, 17])
+        rb.rlhf_kv_arena_free_seq(A.handle, 1)
+        A.model.free_seq(1)
+        for step in range(12):                              # decode steps back to back, no synchronisation
+            rb.rlhf_kv_arena_append(A.handle, [2], [1], extra_k[2][step:step + 1].contiguous(),
+                                    extra_v[2][step:step + 1].contiguous())
+            A.model.append([2], [1])
+        table, hl, free = A.host_state()
+        assert table.tolist() == A.model.page_table() and hl.tolist() == A.model.seq_lens
+        assert free.tolist() == A.model.free
+        d_table, d_lens = _device_mirrors(gu, A)
+        assert d_table == table.tolist() and d_lens == hl.tolist()
+        for b, n in zip(ids, (30, 1, 17)):
+            L = int(lens[b])
+            ko = torch.zeros(n, cfg.n_kv_heads, cfg.head_dim, dtype=ks[0].dtype, device=gu.DEV)
+            vo = torch.zeros_like(ko)
+            rb.rlhf_kv_arena_gather(A.handle, b, L, n, ko, vo)
+            torch.cuda.synchronize()
+            assert _bits_differ(ko, extra_k[b][:n]) == 0 and _bits_differ(vo, extra_v[b][:n]) == 0
+        ko = torch.zeros(12, cfg.n_kv_heads, cfg.head_dim, dtype=ks[0].dtype, device=gu.DEV)
+        vo = torch.zeros_like(ko)
+        rb.rlhf_kv_arena_gather(A.handle, 2, int(lens[2]), 12, ko, vo)
+        torch.cuda.synchronize()
+        assert _bits_differ(ko, extra_k[2][:12]) == 0 and _bits_differ(vo, extra_v[2][:12]) == 0
     finally:
         A.close()
 
@@ -451,6 +528,131 @@ def test_attention_full_size_every_element(gu, oracle, cfg_index):
             vmax = vs[b].float().amax(0)
             o = out[b].view(cfg.n_kv_heads, G, cfg.head_dim)
             assert (o >= vmin[:, None, :] - 1e-5).all() and (o <= vmax[:, None, :] + 1e-5).all()
+    finally:
+        A.close()
+
+
+ONE_LAUNCH_SHAPES = [
+    # shapes with enough (sequence, head) units for the call to be a single launch when run eagerly
+    (2, dict(batch=8, len_lo=0, len_hi=700)),                                   # one head per KV head, D=64
+    (3, dict(batch=6, n_q_heads=40, n_kv_heads=40, len_lo=1, len_hi=300)),      # D=128
+    (5, dict(batch=32, n_q_heads=16, n_kv_heads=8, len_lo=0, len_hi=900)),      # groups of 2
+    (5, dict(batch=24, n_q_heads=64, n_kv_heads=8, len_lo=100, len_hi=1300)),   # groups of 8
+    (1, dict(batch=40, n_q_heads=96, n_kv_heads=4, head_dim=128, len_lo=1, len_hi=200)),   # f16, groups of 24
+]
+
+
+@pytest.mark.parametrize("cfg_index,over", ONE_LAUNCH_SHAPES)
+def test_attention_in_one_launch_and_in_two_is_the_same_bit_for_bit(gu, oracle, cfg_index, over):
+    """Run eagerly the call is one kernel launch (the wavefront that completes a
+    unit merges it); recorded into a graph it is the split kernel and the merge
+    kernel.  Both merge a unit's partials in range order through the same
+    arithmetic, so the outputs must be identical bit for bit, and both must match
+    the oracle.  Which form ran is read off the workspace: only the two-launch
+    form leaves the page-count prefix for its merge kernel there."""
+    cfg = wl.small_variant(wl.config(cfg_index), **over)
+    lens = wl.seq_lengths(cfg)
+    if cfg.len_lo == 0:
+        lens[1] = 0
+        lens[-1] = 0
+    _say(f"one/two launches cfg{cfg_index} {over} lens={lens.tolist()[:12]}...")
+    q, ks, vs = wl.qkv(cfg, lens, device=gu.DEV)
+    A = gu.FilledArena(cfg, lens, ks, vs)
+    try:
+        k, v, table, dl = A.views()
+        host_table, _, _ = A.host_state()
+        expect = gu.oracle_attention(oracle, cfg, q, ks, vs, host_table, lens, A.n_pages)
+        for out_dtype in (rb.RLHF_F32, None):
+            params = rb.attn_params(cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, A.mpps,
+                                    wl.DTYPE_CODE[cfg.kv_dtype], out_dtype=out_dtype)
+            nws = rb.rlhf_decode_attention_workspace_bytes(params)
+            odt = torch.float32 if out_dtype == rb.RLHF_F32 else q.dtype
+            prefix_words = cfg.batch + 1
+
+            def fresh():
+                ws = torch.full((nws,), 0xFF, dtype=torch.uint8, device=gu.DEV)
+                out = torch.full((cfg.batch, cfg.n_q_heads, cfg.head_dim), float("nan"), dtype=odt, device=gu.DEV)
+                return ws, out
+
+            ws1, out1 = fresh()
+            rb.rlhf_decode_attention(params, q, k, v, table, dl, out1, ws1)
+            torch.cuda.synchronize()
+            assert (ws1[:4 * prefix_words] == 0xFF).all(), "the eager call was expected to be one launch"
+            ws2, out2 = fresh()
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=side):
+                rb.rlhf_decode_attention(params, q, k, v, table, dl, out2, ws2, stream=side)
+            for rep in range(2):
+                out2.fill_(float("nan"))
+                torch.cuda.synchronize()
+                graph.replay()
+                torch.cuda.synchronize()
+                pages = ws2[:4 * prefix_words].view(torch.int32)
+                assert int(pages[-1]) == int(((lens.astype(np.int64) + 15) // 16).sum()), "two launches expected"
+                assert _bits_differ(out1, out2) == 0, rep
+            err = np.abs(out1.float().cpu().numpy().astype(np.float64) - expect).max()
+            _say(f"  out {odt}: max-abs err {err:.3e}")
+            assert (out1[lens == 0] == 0).all()
+            if out_dtype == rb.RLHF_F32:
+                assert err <= ATTN_TOL
+            else:
+                assert err <= ATTN_TOL + np.abs(expect).max() * 2.0 ** -8
+    finally:
+        A.close()
+
+
+def test_attention_calls_in_one_launch_from_several_streams_at_once(gu):
+    """The one-launch form keeps arrival counters in device memory of the
+    library's, a set per calling stream.  Four host threads, each on a stream of
+    its own with its own outputs and workspace, call twenty times each at the
+    same time, cycling through four queries; every result must equal the one the
+    same query gives alone."""
+    import threading
+    cfg = wl.small_variant(wl.config(5), batch=32, n_q_heads=16, n_kv_heads=8, len_lo=100, len_hi=900)
+    lens = wl.seq_lengths(cfg)
+    q, ks, vs = wl.qkv(cfg, lens, device=gu.DEV)
+    A = gu.FilledArena(cfg, lens, ks, vs)
+    try:
+        k, v, table, dl = A.views()
+        params = rb.attn_params(cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, A.mpps,
+                                wl.DTYPE_CODE[cfg.kv_dtype], out_dtype=rb.RLHF_F32)
+        nws = rb.rlhf_decode_attention_workspace_bytes(params)
+        qs = [(q.float() * (1.0 - 0.2 * i) + 0.05 * i).to(q.dtype) for i in range(4)]
+        alone = []
+        for qi in qs:
+            ws = torch.full((nws,), 0xFF, dtype=torch.uint8, device=gu.DEV)
+            out = torch.empty(cfg.batch, cfg.n_q_heads, cfg.head_dim, dtype=torch.float32, device=gu.DEV)
+            rb.rlhf_decode_attention(params, qi, k, v, table, dl, out, ws)
+            torch.cuda.synchronize()
+            assert (ws[:4 * (cfg.batch + 1)] == 0xFF).all(), "expected the one-launch form"
+            alone.append(out)
+        assert not torch.equal(alone[0], alone[1])
+        results, errors = {}, []
+
+        def worker(i):
+            try:
+                stream = torch.cuda.Stream()
+                ws = torch.full((nws,), 0xFF, dtype=torch.uint8, device=gu.DEV)
+                outs = [torch.empty_like(alone[0]) for _ in range(20)]
+                torch.cuda.synchronize()
+                for j, o in enumerate(outs):    # two queries in turn through one workspace: a partial
+                    rb.rlhf_decode_attention(params, qs[(i + j) % 4], k, v, table, dl, o, ws, stream=stream)
+                stream.synchronize()            # left over from the call before must never be read
+                results[i] = outs
+            except Exception as e:      # reported by the main thread
+                errors.append(e)
+
+        threads = [threading.Thread(target=worker, args=(i,)) for i in range(4)]
+        for t in threads:
+            t.start()
+        for t in threads:
+            t.join()
+        assert not errors, errors
+        for i in range(4):
+            for j, o in enumerate(results[i]):
+                assert _bits_differ(o, alone[(i + j) % 4]) == 0, (i, j)
     finally:
         A.close()
 
