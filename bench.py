@@ -28,33 +28,45 @@ HBM_PEAK_GBPS = 8000.0     # MI355X, HBM3E
 METRIC = "decode-attn HBM GB/s (% of MI355X peak) + logprob/KL tokens/sec, 1 GPU"
 
 
-# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by a
-# plain 1 GiB copy; see profiles/bench_cfg5_gqa70b_hbm_traffic.txt), valid for workload 5 and
-# only while the kernel sources still hash to the value recorded with them.
-PMC_TRAFFIC = {
-    "logprob_kl": {"sources": ["logprob_kl.hip", "device_ops.h"],
-                   "sha256": "a1c9afe1c3b5699a7b70d09dcbf60deaa55d2f729d0a51b0c248d3537a73b1ad",
-                   "bytes": 67249754465 + 8957520},
-    "decode_attn": {"sources": ["attention.hip", "mfma_ops.h", "device_ops.h"],
-                    "sha256": "3038167cd47bb9fe59b8f058872c80516e2c04efabd33ac95a2651242277b1e0",
-                    "bytes": 1604492489 + 8514888 + 8987273 + 2097152},
-    "prefill_attn": {"sources": ["prefill.hip", "mfma_ops.h", "device_ops.h"],
-                     "sha256": "ee01ae9803199f70b3ead4bf7233c8ca5b205e093f294f01571aca1762142593",
-                     "bytes": 4083248311 + 3322069813},
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by a plain
+# 1 GiB copy) are kept, with the hash of the kernel sources they were taken on, in the lines
+#   traffic <name> workload=<index> bytes=<n> sha256=<hash of the listed sources>
+# of this summary; they hold only while the sources still hash to that value.
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "bench_cfg5_gqa70b_hbm_traffic.txt")
+TRAFFIC_SOURCES = {
+    "logprob_kl": ["logprob_kl.hip", "device_ops.h"],
+    "decode_attn": ["attention.hip", "mfma_ops.h", "device_ops.h"],
+    "prefill_attn": ["prefill.hip", "mfma_ops.h", "device_ops.h"],
 }
 
 
-def measured_traffic(name, cfg_index):
-    """Counter-measured HBM bytes per launch, or None when the kernel has changed
-    since the counters were taken (or for another workload)."""
+def sources_hash(name):
     import hashlib
-    entry = PMC_TRAFFIC[name]
-    if cfg_index != 5:
-        return None
     h = hashlib.sha256()
-    for f in entry["sources"]:
+    for f in TRAFFIC_SOURCES[name]:
         h.update(open(os.path.join(ROOT, "paper_2410_15651_amd", "csrc", f), "rb").read())
-    return entry["bytes"] if h.hexdigest() == entry["sha256"] else None
+    return h.hexdigest()
+
+
+def measured_traffic(name, cfg_index):
+    """Counter-measured HBM bytes per launch from the profile summary, or None --
+    said loudly on stderr -- when the kernel has changed since the counters were
+    taken, or for a workload the summary does not cover."""
+    try:
+        lines = open(TRAFFIC_PROFILE).read().splitlines()
+    except OSError:
+        log(f"bench.py: {TRAFFIC_PROFILE} is missing: roofline traffic of {name} reported as null")
+        return None
+    for line in lines:
+        f = line.split()
+        if len(f) == 5 and f[0] == "traffic" and f[1] == name and f[2] == f"workload={cfg_index}":
+            if f[4] == "sha256=" + sources_hash(name):
+                return int(f[3].split("=")[1])
+            log(f"bench.py: {name} has changed since its HBM counters were taken "
+                f"({os.path.relpath(TRAFFIC_PROFILE, ROOT)}): roofline traffic reported as null; re-run the two "
+                f"rocprofv3 --pmc commands named in that file and update its 'traffic' line")
+            return None
+    return None
 
 
 def log(msg):
@@ -160,6 +172,69 @@ class Workload:
         self.sets = []
 
 
+def time_calls(torch, call, n_calls, n_batches=5, warmup=10):
+    """Per-call time of call(i): `warmup` untimed calls, then `n_batches` batches of
+    `n_calls` calls, each batch between two events on the stream the calls run on.
+    Returns (median, min, max) over the batches, in seconds per call."""
+    for i in range(warmup):
+        call(i)
+    torch.cuda.synchronize()
+    per_call = []
+    k = warmup
+    for _ in range(n_batches):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(n_calls):
+            call(k)
+            k += 1
+        e1.record()
+        torch.cuda.synchronize()
+        per_call.append(e0.elapsed_time(e1) * 1e-3 / n_calls)
+    return float(np.median(per_call)), float(min(per_call)), float(max(per_call))
+
+
+def measure_kernels(wk, n_attn=100, n_logp=100):
+    """Decode attention and log-prob/KL each timed on its own, back to back calls
+    (time_calls): `cold` rotates through the workload's input sets, whose K/V and
+    logits together exceed the last-level cache, `hot` stays on the first set."""
+    rb, torch, cfg = wk.rb, wk.torch, wk.cfg
+    n_sets = len(wk.sets)
+
+    def attn(rotate):
+        def call(i):
+            s = wk.sets[i % n_sets if rotate else 0]
+            k_arena, v_arena, d_table, d_lens = s["views"]
+            rb.rlhf_decode_attention(wk.params, wk.q, k_arena, v_arena, d_table, d_lens, wk.out, wk.ws)
+        return call
+
+    def logp(rotate):
+        def call(i):
+            s = wk.sets[i % n_sets if rotate else 0]
+            rb.rlhf_token_logprobs_kl(s["actor"], s["ref"], wk.tok, wk.logp, wk.kl)
+        return call
+
+    lb = 4 if cfg.logits_dtype == "f32" else 2
+    b_attn = attention_bytes(wk.lens.astype(np.int64) + wk.sets[0]["appended"], cfg)
+    b_logp = logprob_bytes(cfg.n_positions, cfg.vocab, lb)
+    out = {"method": f"median (min..max) of 5 batches; a batch is {n_attn} back-to-back attention calls or "
+                     f"{n_logp} log-prob/KL calls between two events, after 10 warm-up calls",
+           "rotating_input_sets": n_sets}
+    for name, fn, n, nbytes in (("decode_attn", attn, n_attn, b_attn), ("logprob_kl", logp, n_logp, b_logp)):
+        for mode, rotate in (("cold", True), ("hot", False)):
+            med, lo, hi = time_calls(torch, fn(rotate), n)
+            out[f"{name}_{mode}_us"] = round(med * 1e6, 2)
+            out[f"{name}_{mode}_us_min_max"] = [round(lo * 1e6, 2), round(hi * 1e6, 2)]
+            out[f"{name}_{mode}_GBps"] = round(nbytes / med / 1e9, 1)
+            out[f"{name}_{mode}_frac_of_peak"] = round(nbytes / med / 1e9 / HBM_PEAK_GBPS, 4)
+    out["logprob_kl_cold_tokens_per_s"] = round(cfg.n_positions / (out["logprob_kl_cold_us"] * 1e-6), 1)
+    kv = n_sets * 2 * int(wk.lens.sum()) * cfg.n_kv_heads * cfg.head_dim * 2
+    lg = n_sets * 2 * cfg.n_positions * cfg.vocab * lb
+    out["cold_means"] = (f"rotation over {n_sets} input set(s): {kv / 1e6:.0f} MB of K/V and {lg / 1e6:.0f} MB of logits "
+                         f"between two uses of the same bytes" +
+                         ("" if kv > 512e6 else "; K/V rotation stays under 512 MB (capped at 12 sets): partly cache-resident"))
+    return out
+
+
 def rotation_sets(cfg):
     """Copies needed so that the rotated K/V and the rotated logits each exceed
     512 MB (more than the last-level cache holds), capped at 12."""
@@ -170,13 +245,17 @@ def rotation_sets(cfg):
     return int(min(12, max(1, np.ceil(need))))
 
 
+APPEND_CALLS = 10 + 5 * 100      # time_calls on the append: warm-up + five batches of a hundred
+
+
 def measure(cfg, K, W, dev):
-    """Times K steps after W warm-up steps; returns the numbers of one configuration."""
+    """Times K steps after W warm-up steps, then each kernel on its own
+    (measure_kernels); returns the numbers of one configuration."""
     import torch
     lb = 4 if cfg.logits_dtype == "f32" else 2
     n_sets = rotation_sets(cfg)
     t0 = time.time()
-    wk = Workload(cfg, K + W, n_sets, dev)
+    wk = Workload(cfg, K + W + APPEND_CALLS, n_sets, dev)
     log(f"setup {time.time() - t0:.1f}s: cfg{cfg.index} {cfg.name}, {n_sets} rotating input set(s), K/V "
         f"{2 * wk.lens.sum() * cfg.n_kv_heads * cfg.head_dim * 2 / 1e9:.3f} GB, logits "
         f"{2 * cfg.n_positions * cfg.vocab * lb / 1e9:.2f} GB, arena reserved {wk.arena_bytes / 1e9:.3f} GB each")
@@ -192,6 +271,13 @@ def measure(cfg, K, W, dev):
     t_append = np.array([m[0][0].elapsed_time(m[0][1]) for m in marks]) * 1e-3
     t_attn = np.array([m[0][1].elapsed_time(m[0][2]) for m in marks]) * 1e-3
     t_logp = np.array([m[0][2].elapsed_time(m[0][3]) for m in marks]) * 1e-3
+    t_step = np.array([m[0][0].elapsed_time(m[0][3]) for m in marks]) * 1e-3
+    kernels = measure_kernels(wk, n_logp=10 if 2 * cfg.n_positions * cfg.vocab * lb > 16e9 else 100)
+    s0 = wk.sets[0]
+    med, lo, hi = time_calls(torch, lambda i: wk.rb.rlhf_kv_arena_append(s0["arena"], wk.seq_ids, wk.ones, wk.step_k,
+                                                                          wk.step_v), 100)
+    kernels["append_us"] = round(med * 1e6, 2)
+    kernels["append_us_min_max"] = [round(lo * 1e6, 2), round(hi * 1e6, 2)]
     b_attn = float(np.mean([m[1] for m in marks]))
     b_logp = logprob_bytes(cfg.n_positions, cfg.vocab, lb)
     b_step = b_attn + b_logp + append_bytes(cfg)
@@ -223,7 +309,12 @@ def measure(cfg, K, W, dev):
         ms_per_step=t_total / K * 1e3, value=b_step / (t_total / K) / 1e9,
         attn_gbps=b_attn / t_attn.mean() / 1e9, logp_gbps=b_logp / t_logp.mean() / 1e9,
         attn_us=t_attn.mean() * 1e6, logp_us=t_logp.mean() * 1e6, append_us=t_append.mean() * 1e6,
-        sample_us=sample_us, topk_us=topk_us, attn_cold=bool(kv_rotated > 512e6), stats=wk.rb.rlhf_kv_arena_stats(wk.sets[0]["arena"]))
+        sample_us=sample_us, topk_us=topk_us, attn_cold=bool(kv_rotated > 512e6), kernels=kernels,
+        per_step={"step_ms": [round(float(x) * 1e3, 4) for x in (t_step.min(), np.median(t_step), t_step.max())],
+                  "decode_attn_us": [round(float(x) * 1e6, 2) for x in (t_attn.min(), np.median(t_attn), t_attn.max())],
+                  "logprob_kl_us": [round(float(x) * 1e6, 2) for x in (t_logp.min(), np.median(t_logp), t_logp.max())],
+                  "order": "min, median, max over the timed steps (events around every call of every step)"},
+        stats=wk.rb.rlhf_kv_arena_stats(wk.sets[0]["arena"]))
     return res
 
 
@@ -369,11 +460,14 @@ def main():
             "sample_tokens_top50_us_per_decode_step": round(m["topk_us"], 2),
             "arena_reserved_bytes": stats["reserved_bytes"], "arena_allocated_bytes": stats["allocated_bytes"],
             "arena_driver_allocations_after_create": 0,
+            "per_step_distribution": m["per_step"],
+            "kernels_back_to_back": m["kernels"],
         },
         "roofline": {"kernel": "logprob_kl_kernel", "bound": "hbm", "achieved": round(m["logp_gbps"], 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(m["logp_gbps"] / HBM_PEAK_GBPS, 4),
                      "traffic": measured_traffic("logprob_kl", cfg.index)},
-        "roofline_decode_attn": {"kernel": attn_kernel + "+attn_merge_kernel", "bound": "hbm",
+        "roofline_decode_attn": {"kernel": attn_kernel + " (one launch: the wavefront that completes a unit merges it)",
+                                 "bound": "hbm",
                                  "achieved": round(m["attn_gbps"], 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                                  "frac": round(m["attn_gbps"] / HBM_PEAK_GBPS, 4),
                                  "traffic": measured_traffic("decode_attn", cfg.index)},
@@ -406,19 +500,18 @@ def main():
             if c.index == cfg.index:
                 continue
             o = measure(c, 10, 2, dev)
+            kb = o["kernels"]
             others.append({
-                "workload": f"configs[{c.index - 1}] {c.name}", "rotating_input_sets": o["n_sets"],
-                "decode_attn_us": round(o["attn_us"], 2), "decode_attn_GBps": round(o["attn_gbps"], 1),
-                "decode_attn_frac_of_peak": round(o["attn_gbps"] / HBM_PEAK_GBPS, 4),
-                "decode_attn_reads": "cold (rotated past the last-level cache)" if o["attn_cold"]
-                                     else "cache-resident: the call is launch-latency-bound",
-                "logprob_kl_us": round(o["logp_us"], 2),
-                "logprob_kl_tokens_per_s": round(c.n_positions / (o["logp_us"] * 1e-6), 1),
-                "logprob_kl_GBps": round(o["logp_gbps"], 1),
-                "logprob_kl_frac_of_peak": round(o["logp_gbps"] / HBM_PEAK_GBPS, 4),
-                "append_us": round(o["append_us"], 2), "sample_tokens_us": round(o["sample_us"], 2),
+                "workload": f"configs[{c.index - 1}] {c.name}", "method": kb["method"],
+                "rotating_input_sets": o["n_sets"], "cold_means": kb["cold_means"],
+                **{k: v for k, v in kb.items() if k.startswith(("decode_attn_", "logprob_kl_", "append_"))},
+                "sample_tokens_us": round(o["sample_us"], 2),
                 "sample_tokens_top50_us": round(o["topk_us"], 2),
-                "step_GBps": round(o["value"], 1)})
+                "step_loop": {"steps": 10, "warmup": 2, "step_GBps": round(o["value"], 1),
+                              "decode_attn_us": round(o["attn_us"], 2), "logprob_kl_us": round(o["logp_us"], 2),
+                              "append_us": round(o["append_us"], 2),
+                              "note": "mean of 10 steps with events around every call (includes the launch "
+                                      "latency of a lone call)"}})
             o["wk"].close()
             del o
             torch.cuda.empty_cache()
