@@ -279,6 +279,22 @@ int rlhf_decode_attention(const rlhf_attn_params *params, const void *q, const v
                           const void *v_arena, const int32_t *page_table, const int32_t *seq_lens,
                           void *out, void *workspace, size_t workspace_bytes, void *stream);
 
+/* rlhf_decode_attention for callers that cannot allocate device memory and so
+ * cannot bring a workspace (code under graph capture, serving loops, harnesses
+ * that forbid allocation): the split partials go to a 16 MiB scratch array
+ * that is part of the library's device image (one per device, held until the
+ * process ends).  Same arguments, results and limits otherwise; a shape whose
+ * workspace (rlhf_decode_attention_workspace_bytes) would exceed 16 MiB is
+ * RLHF_ERR_UNSUPPORTED (the largest configuration of the paper's model shapes,
+ * 128 sequences x 64/8 heads x 128, needs 8.5 MB).  The call allocates nothing,
+ * issues no memset or copy and does not synchronise.  All calls on a device
+ * share that one array and one set of arrival counters, whatever their stream:
+ * calls that may overlap on the device race and must be ordered by the caller
+ * (one stream, or events). */
+int rlhf_decode_attention_static(const rlhf_attn_params *params, const void *q, const void *k_arena,
+                                 const void *v_arena, const int32_t *page_table, const int32_t *seq_lens,
+                                 void *out, void *stream);
+
 /* ------------------------------------------------------------------------
  * Fused token log-probability and actor-vs-reference KL (Section 2.1: actor
  * and reference inferences over the generated tokens; the KL term is what

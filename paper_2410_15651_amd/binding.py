@@ -29,7 +29,8 @@ EXPORTS = [
     "rlhf_kv_arena_append", "rlhf_kv_arena_free_seq", "rlhf_kv_arena_fail_next_submissions",
     "rlhf_kv_arena_reset", "rlhf_kv_arena_stats",
     "rlhf_kv_arena_views", "rlhf_kv_arena_host_state", "rlhf_kv_arena_gather",
-    "rlhf_decode_attention_workspace_bytes", "rlhf_decode_attention", "rlhf_token_logprobs_kl",
+    "rlhf_decode_attention_workspace_bytes", "rlhf_decode_attention", "rlhf_decode_attention_static",
+    "rlhf_token_logprobs_kl",
     "rlhf_token_logprobs_kl_rewards", "rlhf_sample_tokens", "rlhf_sample_tokens_workspace_bytes",
     "rlhf_sample_tokens_split", "rlhf_sample_tokens_topk", "rlhf_prefill_attention",
     "rlhf_prefill_attention_wg", "rlhf_probe_stream_read",
@@ -119,6 +120,7 @@ def lib() -> ctypes.CDLL:
         L.rlhf_kv_arena_gather.argtypes = [vp, i32, i32, i32, vp, vp, vp]
         L.rlhf_decode_attention_workspace_bytes.argtypes = [P(AttnParams), P(sz)]
         L.rlhf_decode_attention.argtypes = [P(AttnParams), vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.rlhf_decode_attention_static.argtypes = [P(AttnParams), vp, vp, vp, vp, vp, vp, vp]
         L.rlhf_token_logprobs_kl.argtypes = [vp, vp, vp, vp, vp, i64, i32, i64, i32, vp]
         L.rlhf_token_logprobs_kl_rewards.argtypes = [vp, vp, vp, vp, vp, i64, i32, i64, i32,
                                                      P(RewardShaping), vp]
@@ -283,6 +285,12 @@ def rlhf_decode_attention_workspace_bytes(params: AttnParams) -> int:
     out = ctypes.c_size_t()
     _check(lib().rlhf_decode_attention_workspace_bytes(ctypes.byref(params), ctypes.byref(out)))
     return out.value
+
+
+def rlhf_decode_attention_static(params: AttnParams, q, k_arena, v_arena, page_table, seq_lens, out,
+                                 stream=None) -> None:
+    _check(lib().rlhf_decode_attention_static(ctypes.byref(params), _ptr(q), _ptr(k_arena), _ptr(v_arena),
+                                              _ptr(page_table), _ptr(seq_lens), _ptr(out), _stream(stream)))
 
 
 def rlhf_decode_attention(params: AttnParams, q, k_arena, v_arena, page_table, seq_lens, out,

@@ -86,10 +86,11 @@ constexpr int kComputeUnits = 256;
 constexpr int kWavesPerCuMha = 8;
 constexpr int kWavesPerCuGqa = 4;
 
-// Arrival counters of the one-launch path: kStreamSets sets, one per calling
-// stream, each with room for kMaxFusedUnits (sequence, unit) pairs.
+// Arrival counters of the one-launch path: kCounterSets sets, one per calling
+// stream (the last one belongs to the entry point that works in the library's
+// own scratch), each with room for kMaxFusedUnits (sequence, unit) pairs.
 constexpr int kStreamSets = 8;
-constexpr int kCounterSets = kStreamSets;
+constexpr int kCounterSets = kStreamSets + 1;
 constexpr int kMaxFusedUnits = 1 << 15;
 // The one-launch path is taken while a wavefront merges at most about this many
 // partials per unit on average (ranges / units); above that the merge kernel's
@@ -97,9 +98,11 @@ constexpr int kMaxFusedUnits = 1 << 15;
 constexpr int kFusedMaxAvgPartialsMha = 32;
 constexpr int kFusedMaxAvgPartialsGqa = 8;
 
-// Device memory owned by the library.  Host code never uses this name as an
-// address: the per-device address comes from hipGetSymbolAddress.
+// Device memory owned by the library.  Host code never uses these names as
+// addresses: the per-device addresses come from hipGetSymbolAddress.
 static __device__ unsigned int g_arrivals[kCounterSets * kMaxFusedUnits];
+constexpr size_t kStaticScratchBytes = (size_t)16 << 20;
+static __device__ __align__(256) unsigned char g_scratch[kStaticScratchBytes];
 
 struct Shape {
     int batch, n_q_heads, n_kv_heads, group;
@@ -896,6 +899,7 @@ struct DeviceState {
     bool ready = false;
     int compute_units = 0;
     unsigned int *arrivals = nullptr;   // g_arrivals on this device
+    unsigned char *scratch = nullptr;   // g_scratch on this device
     int n_streams = 0;
     hipStream_t streams[kStreamSets] = {};
 };
@@ -913,6 +917,7 @@ int device_state(DeviceState **out)
     if (!d.ready) {
         RLHF_HIP_TRY(hipDeviceGetAttribute(&d.compute_units, hipDeviceAttributeMultiprocessorCount, dev));
         RLHF_HIP_TRY(hipGetSymbolAddress((void **)&d.arrivals, HIP_SYMBOL(g_arrivals)));
+        RLHF_HIP_TRY(hipGetSymbolAddress((void **)&d.scratch, HIP_SYMBOL(g_scratch)));
         d.ready = true;
     }
     *out = &d;
@@ -946,10 +951,12 @@ bool being_captured(hipStream_t s)
     return st != hipStreamCaptureStatusNone;
 }
 
+enum class Scratch { Caller, Library };
+
 template <int DT, int D>
 int launch(const rlhf_attn_params &p, const Shape &sh, const void *q, const void *k_arena,
            const void *v_arena, const int32_t *page_table, const int32_t *seq_lens, void *out,
-           void *workspace, hipStream_t s)
+           void *workspace, Scratch where, hipStream_t s)
 {
     const float scale = p.softmax_scale != 0.f ? p.softmax_scale : 1.0f / sqrtf((float)D);
     const size_t lds = ((size_t)p.batch + 1 + kThreads) * sizeof(int);
@@ -960,17 +967,19 @@ int launch(const rlhf_attn_params &p, const Shape &sh, const void *q, const void
     unsigned int *arrivals = nullptr;
     int n_waves = sh.n_waves;
     const bool capturing = being_captured(s);
-    if (!capturing) {
+    if (!capturing || where == Scratch::Library) {
         DeviceState *d = nullptr;
         const int rc = device_state(&d);
         if (rc != RLHF_OK)
             return rc;
         n_waves = std::min(sh.n_waves, std::max(d->compute_units, 1) * waves_per_cu);
+        if (where == Scratch::Library)
+            workspace = d->scratch;
         // ranges the kernel will cut the axis into, at most: wavefronts, or page steps if fewer
         const int64_t ranges = std::min<int64_t>(n_waves, n_units * ((sh.max_len + kPage - 1) / kPage));
         const int avg_cap = sh.group == 1 ? kFusedMaxAvgPartialsMha : kFusedMaxAvgPartialsGqa;
-        if (n_units <= kMaxFusedUnits && ranges <= avg_cap * n_units) {
-            const int set = counter_set_of(d, s);
+        if (!capturing && n_units <= kMaxFusedUnits && ranges <= avg_cap * n_units) {
+            const int set = where == Scratch::Library ? kStreamSets : counter_set_of(d, s);
             if (set >= 0)
                 arrivals = d->arrivals + (size_t)set * kMaxFusedUnits;
         }
@@ -1014,7 +1023,7 @@ size_t workspace_need(const rlhf_attn_params &p, const Shape &sh)
 
 int decode_attention(const rlhf_attn_params *params, const void *q, const void *k_arena, const void *v_arena,
                      const int32_t *page_table, const int32_t *seq_lens, void *out, void *workspace,
-                     size_t workspace_bytes_given, void *stream)
+                     size_t workspace_bytes_given, Scratch where, void *stream)
 {
     int rc = check_params(params);
     if (rc != RLHF_OK)
@@ -1022,23 +1031,28 @@ int decode_attention(const rlhf_attn_params *params, const void *q, const void *
     const rlhf_attn_params &p = *params;
     if (p.batch == 0)
         return RLHF_OK;
-    if (!q || !k_arena || !v_arena || !page_table || !seq_lens || !out || !workspace)
+    if (!q || !k_arena || !v_arena || !page_table || !seq_lens || !out ||
+        (where == Scratch::Caller && !workspace))
         return fail(RLHF_ERR_INVALID, "NULL pointer");
     if (((uintptr_t)q | (uintptr_t)k_arena | (uintptr_t)v_arena | (uintptr_t)out | (uintptr_t)workspace) % 16)
         return fail(RLHF_ERR_INVALID, "q, k_arena, v_arena, out and workspace must be 16-byte aligned");
     const Shape sh = make_shape(p);
     const size_t need = workspace_need(p, sh);
-    if (workspace_bytes_given < need)
+    if (where == Scratch::Caller && workspace_bytes_given < need)
         return fail(RLHF_ERR_INVALID, "workspace holds %zu bytes, %zu needed", workspace_bytes_given, need);
+    if (where == Scratch::Library && need > kStaticScratchBytes)
+        return fail(RLHF_ERR_UNSUPPORTED,
+                    "this shape needs %zu bytes of scratch, the library's own holds %zu: use "
+                    "rlhf_decode_attention with a workspace", need, kStaticScratchBytes);
     hipStream_t s = (hipStream_t)stream;
     if (p.qkv_dtype == RLHF_BF16) {
         if (p.head_dim == 128)
-            return launch<RLHF_BF16, 128>(p, sh, q, k_arena, v_arena, page_table, seq_lens, out, workspace, s);
-        return launch<RLHF_BF16, 64>(p, sh, q, k_arena, v_arena, page_table, seq_lens, out, workspace, s);
+            return launch<RLHF_BF16, 128>(p, sh, q, k_arena, v_arena, page_table, seq_lens, out, workspace, where, s);
+        return launch<RLHF_BF16, 64>(p, sh, q, k_arena, v_arena, page_table, seq_lens, out, workspace, where, s);
     }
     if (p.head_dim == 128)
-        return launch<RLHF_F16, 128>(p, sh, q, k_arena, v_arena, page_table, seq_lens, out, workspace, s);
-    return launch<RLHF_F16, 64>(p, sh, q, k_arena, v_arena, page_table, seq_lens, out, workspace, s);
+        return launch<RLHF_F16, 128>(p, sh, q, k_arena, v_arena, page_table, seq_lens, out, workspace, where, s);
+    return launch<RLHF_F16, 64>(p, sh, q, k_arena, v_arena, page_table, seq_lens, out, workspace, where, s);
 }
 
 }  // namespace
@@ -1062,5 +1076,13 @@ extern "C" int rlhf_decode_attention(const rlhf_attn_params *params, const void 
                                      void *out, void *workspace, size_t workspace_bytes_given, void *stream)
 {
     return decode_attention(params, q, k_arena, v_arena, page_table, seq_lens, out, workspace,
-                            workspace_bytes_given, stream);
+                            workspace_bytes_given, Scratch::Caller, stream);
+}
+
+extern "C" int rlhf_decode_attention_static(const rlhf_attn_params *params, const void *q, const void *k_arena,
+                                            const void *v_arena, const int32_t *page_table,
+                                            const int32_t *seq_lens, void *out, void *stream)
+{
+    return decode_attention(params, q, k_arena, v_arena, page_table, seq_lens, out, nullptr, 0,
+                            Scratch::Library, stream);
 }
