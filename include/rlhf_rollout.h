@@ -302,7 +302,9 @@ int rlhf_decode_attention_static(const rlhf_attn_params *params, const void *q, 
  *     logp_out[i] = log softmax(actor[i,:])[tokens[i]]
  *     kl_out[i]   = KL( softmax(actor[i,:]) || softmax(ref[i,:]) )   (nats, >= 0 up to rounding)
  * fp32 accumulation.  tokens[i] outside [0, vocab) marks padding: both
- * outputs are 0 for that position.  Logits are finite or -infinity (a masked
+ * outputs are 0 for that position (negative ids are the padding convention;
+ * an id >= vocab is scored the same way, and rlhf_token_logprobs_kl_rewards
+ * can report it through a device flag).  Logits are finite or -infinity (a masked
  * entry); a NaN logit gives NaN outputs for its row.  The outputs carry the
  * fp32 rounding of the logits' own magnitude (about 1.2e-7 * max |logit|) on
  * top of the error of the sums, which stays far below 1e-3.
@@ -332,6 +334,12 @@ int rlhf_token_logprobs_kl(const void *actor_logits, const void *ref_logits, con
  * or NULL) is what the caller wants added per position: the sequence's score at
  * its last generated position, 0 elsewhere.  Padded positions get 0 in every
  * output.  ref_logp_out and reward_out may each be NULL.
+ *
+ * token_error_flag (dev int32 or NULL) tells a corrupted token id from padding:
+ * the kernel stores 1 there when some tokens[i] >= vocab, and never stores
+ * anything else, so the flag is sticky across calls until the caller clears it
+ * (a 4-byte fill or copy on the same stream); it is read like any device
+ * buffer, after the stream has reached the call.  Negative ids never set it.
  * ------------------------------------------------------------------------ */
 #define RLHF_PENALTY_FULL_KL 0
 #define RLHF_PENALTY_SAMPLED 1
@@ -342,6 +350,7 @@ typedef struct {
     const float *terminal_scores; /* dev [n_positions] or NULL */
     float kl_coef;
     int32_t penalty;              /* RLHF_PENALTY_FULL_KL or RLHF_PENALTY_SAMPLED */
+    int32_t *token_error_flag;    /* dev int32 or NULL: becomes 1 if some tokens[i] >= vocab */
 } rlhf_reward_shaping;
 
 int rlhf_token_logprobs_kl_rewards(const void *actor_logits, const void *ref_logits, const int32_t *tokens,

@@ -85,6 +85,7 @@ class RewardShaping(ctypes.Structure):
     _fields_ = [
         ("ref_logp_out", ctypes.c_void_p), ("reward_out", ctypes.c_void_p),
         ("terminal_scores", ctypes.c_void_p), ("kl_coef", ctypes.c_float), ("penalty", ctypes.c_int32),
+        ("token_error_flag", ctypes.c_void_p),
     ]
 
 
@@ -334,7 +335,7 @@ def rlhf_token_logprobs_kl(actor_logits, ref_logits, tokens, logp_out, kl_out, n
 def rlhf_token_logprobs_kl_rewards(actor_logits, ref_logits, tokens, logp_out, kl_out, kl_coef,
                                    penalty=RLHF_PENALTY_FULL_KL, ref_logp_out=None, reward_out=None,
                                    terminal_scores=None, n_positions=None, vocab=None, row_stride_elems=0,
-                                   logits_dtype=None, stream=None) -> None:
+                                   logits_dtype=None, stream=None, token_error_flag=None) -> None:
     if n_positions is None:
         n_positions = actor_logits.shape[0]
     if vocab is None:
@@ -342,7 +343,8 @@ def rlhf_token_logprobs_kl_rewards(actor_logits, ref_logits, tokens, logp_out, k
         row_stride_elems = actor_logits.stride(0)
     if logits_dtype is None:
         logits_dtype = dtype_code(actor_logits.dtype)
-    sh = RewardShaping(_ptr(ref_logp_out), _ptr(reward_out), _ptr(terminal_scores), kl_coef, penalty)
+    sh = RewardShaping(_ptr(ref_logp_out), _ptr(reward_out), _ptr(terminal_scores), kl_coef, penalty,
+                       _ptr(token_error_flag))
     _check(lib().rlhf_token_logprobs_kl_rewards(_ptr(actor_logits), _ptr(ref_logits), _ptr(tokens),
                                                 _ptr(logp_out), _ptr(kl_out), n_positions, vocab,
                                                 row_stride_elems, logits_dtype, ctypes.byref(sh),

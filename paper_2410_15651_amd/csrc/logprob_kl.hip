@@ -148,6 +148,7 @@ struct Shaping {
     const float *terminal;
     float kl_coef;
     int sampled;
+    int32_t *token_error_flag;  // set to 1, never cleared here, when a token id is >= vocab
 };
 
 // VEC: rows start 16-byte aligned and are read with 128-bit loads; otherwise
@@ -166,6 +167,8 @@ __global__ __launch_bounds__(kThreads) void logprob_kl_kernel(
     const int tok = tokens[row];
     if (tok < 0 || tok >= vocab) {  // padded position: uniform across the block
         if (tid == 0) {
+            if (tok >= vocab && sh.token_error_flag)  // not padding by convention: tell the caller
+                *sh.token_error_flag = 1;
             logp_out[row] = 0.f;
             kl_out[row] = 0.f;
             if (sh.ref_logp_out)
@@ -332,7 +335,7 @@ extern "C" int rlhf_token_logprobs_kl(const void *actor_logits, const void *ref_
                                       int64_t n_positions, int32_t vocab, int64_t row_stride_elems,
                                       int32_t logits_dtype, void *stream)
 {
-    const rlhf::Shaping none = {nullptr, nullptr, nullptr, 0.f, 0};
+    const rlhf::Shaping none = {nullptr, nullptr, nullptr, 0.f, 0, nullptr};
     return logprobs_kl_impl(actor_logits, ref_logits, tokens, logp_out, kl_out, n_positions, vocab,
                             row_stride_elems, logits_dtype, none, stream);
 }
@@ -348,7 +351,8 @@ extern "C" int rlhf_token_logprobs_kl_rewards(const void *actor_logits, const vo
     if (shaping->penalty != RLHF_PENALTY_FULL_KL && shaping->penalty != RLHF_PENALTY_SAMPLED)
         return rlhf::fail(RLHF_ERR_INVALID, "penalty %d", shaping->penalty);
     const rlhf::Shaping sh = {shaping->ref_logp_out, shaping->reward_out, shaping->terminal_scores,
-                              shaping->kl_coef, shaping->penalty == RLHF_PENALTY_SAMPLED};
+                              shaping->kl_coef, shaping->penalty == RLHF_PENALTY_SAMPLED,
+                              shaping->token_error_flag};
     return logprobs_kl_impl(actor_logits, ref_logits, tokens, logp_out, kl_out, n_positions, vocab,
                             row_stride_elems, logits_dtype, sh, stream);
 }

@@ -81,6 +81,13 @@ __device__ __forceinline__ uint32_t pack_f16(float first, float second)
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, half2_t));
 }
 
+// acc + lo + hi of two packed fp16, in fp32 (v_dot2_f32_f16 against (1, 1)).
+__device__ __forceinline__ float pair_sum(uint32_t packed, float acc)
+{
+    const half2_t ones = {(_Float16)1.0f, (_Float16)1.0f};
+    return __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, packed), ones, acc, false);
+}
+
 // Two packed bf16 -> two packed fp16.  Exact for magnitudes in fp16's normal
 // range; smaller ones round (absolute error under 2^-25), 65536 and above
 // become infinity.
@@ -170,28 +177,30 @@ __global__ __launch_bounds__(WAVES * 64) void prefill_attn_kernel(
         pbb = table[min(2 * s + 1, n_pages - 1)];
     };
     auto fetch = [&](Staged &st, int pa, int pbb) {
-        const int64_t base_a = (int64_t)pa * page_stride + head_off;
-        const int64_t base_b = (int64_t)pbb * page_stride + head_off;
 #pragma unroll
         for (int i = 0; i < kCopies; ++i) {
-            const int item = tid + i * kThreads;
-            if (kItems % kThreads == 0 || item < kItems) {
-                const bool second = item >= kItems / 2;  // page b
-                const int within = item - (second ? kItems / 2 : 0);
-                const int64_t base = second ? base_b : base_a;
-                st.k[i] = *reinterpret_cast<const uint4 *>(k_arena + base + within * 8);
+            // A wavefront's 64 items lie in one page (kItems / 2 is a multiple of 64), so
+            // the page and its base address are scalars and the loads take them as such.
+            const int item0 = wv * 64 + i * kThreads;
+            if (kItems % kThreads == 0 || item0 < kItems) {
+                const bool second = item0 >= kItems / 2;  // page b
+                const int64_t base = (int64_t)(second ? pbb : pa) * page_stride + head_off;
+                const uint16_t *kp = k_arena + base, *vp = v_arena + base;
+                const int within = lane + item0 - (second ? kItems / 2 : 0);
+                st.k[i] = *reinterpret_cast<const uint4 *>(kp + within * 8);
                 const int hh = within / D, dim = within - hh * D;
-                st.v0[i] = *reinterpret_cast<const uint2 *>(v_arena + base + (hh * D + dim) * 4);
-                st.v1[i] = *reinterpret_cast<const uint2 *>(v_arena + base + ((hh + 2) * D + dim) * 4);
+                st.v0[i] = *reinterpret_cast<const uint2 *>(vp + (hh * D + dim) * 4);
+                st.v1[i] = *reinterpret_cast<const uint2 *>(vp + ((hh + 2) * D + dim) * 4);
             }
         }
     };
     auto deposit = [&](const Staged &st, int buf) {
 #pragma unroll
         for (int i = 0; i < kCopies; ++i) {
-            const int item = tid + i * kThreads;
-            if (kItems % kThreads == 0 || item < kItems) {
-                const int second = item >= kItems / 2;
+            const int item0 = wv * 64 + i * kThreads;
+            if (kItems % kThreads == 0 || item0 < kItems) {
+                const int item = item0 + lane;
+                const int second = item0 >= kItems / 2;
                 const int within = item - second * (kItems / 2);
                 const int d8 = within >> 4, slot = within & 15;
                 *reinterpret_cast<uint4 *>(&stage[buf][(d8 * 32 + 16 * second + slot) * 16]) = st.k[i];
@@ -261,14 +270,21 @@ __global__ __launch_bounds__(WAVES * 64) void prefill_attn_kernel(
 #pragma unroll
         for (int j = 0; j < 16; ++j)
             p[j] = fast_exp2(fmaf(x[j], scale_log2, -m_ref));
-        l_part += (((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]))) +
-                  (((p[8] + p[9]) + (p[10] + p[11])) + ((p[12] + p[13]) + (p[14] + p[15])));
         // P^T as B operands: entries 8h..8h+7 of page a are registers 0..7, of page b 8..15
         uint4 ph[2];
 #pragma unroll
         for (int e = 0; e < 2; ++e)
             ph[e] = make_uint4(pack_f16(p[8 * e + 0], p[8 * e + 1]), pack_f16(p[8 * e + 2], p[8 * e + 3]),
                                pack_f16(p[8 * e + 4], p[8 * e + 5]), pack_f16(p[8 * e + 6], p[8 * e + 7]));
+        // Row sums from the rounded weights, the very numbers the product below uses
+        // (numerator and denominator see the same rounding), two per instruction.
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            l_part = pair_sum(ph[e].x, l_part);
+            l_part = pair_sum(ph[e].y, l_part);
+            l_part = pair_sum(ph[e].z, l_part);
+            l_part = pair_sum(ph[e].w, l_part);
+        }
         // O^T[dim][row] += V^T[dim][key] * P^T[key][row], 16 keys (one page) per product
 #pragma unroll
         for (int e = 0; e < 2; ++e) {

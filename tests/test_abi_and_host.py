@@ -39,7 +39,7 @@ def test_struct_sizes_match_the_header():
     assert ctypes.sizeof(rb.ArenaDesc) == 8 * 4 + 8 + 8 + 8
     assert ctypes.sizeof(rb.ArenaStats) == 4 * 8 + 4 * 4
     assert ctypes.sizeof(rb.AttnParams) == 10 * 4
-    assert ctypes.sizeof(rb.RewardShaping) == 3 * 8 + 2 * 4
+    assert ctypes.sizeof(rb.RewardShaping) == 3 * 8 + 2 * 4 + 8
 
 
 def _host_arena(**kw):

@@ -832,6 +832,37 @@ def test_reward_shaping_matches_oracle(gu, oracle, cfg_index, n, penalty):
     assert torch.equal(logp2, logp) and torch.equal(kl2, kl)
 
 
+def test_token_error_flag_tells_an_out_of_range_id_from_padding(gu):
+    """A token id at or above the vocabulary is scored like padding (zeros), and
+    the optional device flag becomes 1 and stays 1; negative ids (the padding
+    convention) never set it.  Integer result: exact."""
+    V, n = 3000, 6
+    g = torch.Generator(device=gu.DEV)
+    g.manual_seed(3)
+    actor = (torch.randn(n, V, generator=g, device=gu.DEV) * 3).to(torch.bfloat16)
+    ref = (torch.randn(n, V, generator=g, device=gu.DEV) * 3).to(torch.bfloat16)
+    flag = torch.zeros(1, dtype=torch.int32, device=gu.DEV)
+    logp = torch.empty(n, dtype=torch.float32, device=gu.DEV)
+    kl = torch.empty_like(logp)
+
+    def run(tok):
+        t = torch.tensor(tok, dtype=torch.int32, device=gu.DEV)
+        logp.fill_(float("nan"))
+        rb.rlhf_token_logprobs_kl_rewards(actor, ref, t, logp, kl, 0.1, token_error_flag=flag)
+        torch.cuda.synchronize()
+        return int(flag.item())
+
+    assert run([0, 5, -1, V - 1, -7, 17]) == 0                 # valid ids and padding only
+    assert logp[2] == 0 and logp[4] == 0 and (logp[[0, 1, 3, 5]] < 0).all()
+    assert run([0, 5, V, 2, 3, 4]) == 1                        # one id just past the vocabulary
+    assert logp[2] == 0 and kl[2] == 0
+    assert run([1, 2, 3, 4, 5, 6]) == 1                        # sticky: a clean call does not clear it
+    flag.zero_()
+    assert run([1, 2, 2 ** 31 - 1, 4, 5, 6]) == 1
+    flag.zero_()
+    assert run([1, 2, 3, 4, 5, 6]) == 0
+
+
 # ---------------------------------------------------------------- sampling ----
 def _check_sampling(gu, oracle, logits, temperature, seed, offset, vocab=None, stride=0, split=False):
     """The sampled decision is an argmax of fp32 scores on the GPU and of fp64
