@@ -112,32 +112,46 @@ __device__ __forceinline__ void accumulate(RowSums &st, const float (&a)[N], con
     }
 }
 
-__device__ __forceinline__ float block_max(float v, float *lds)
+// Maxima of two values and sums of three over the workgroup, one barrier each
+// (a row's five reductions cost two barriers instead of ten: with a workgroup per
+// row nothing is in flight while a row is being finished, so that time is lost
+// bandwidth).  Every thread gets the results; the four wavefronts' partial
+// results are combined in wavefront order by everybody, so all threads agree.
+__device__ __forceinline__ void block_max2(float &a, float &b, float *lds)
 {
-    const float w = wave_max(v);
-    if ((threadIdx.x & 63) == 0)
-        lds[threadIdx.x >> 6] = w;
+    const float wa = wave_max(a), wb = wave_max(b);
+    if ((threadIdx.x & 63) == 0) {
+        lds[threadIdx.x >> 6] = wa;
+        lds[kWaves + (threadIdx.x >> 6)] = wb;
+    }
     __syncthreads();
-    float r = lds[0];
+    a = lds[0];
+    b = lds[kWaves];
 #pragma unroll
-    for (int k = 1; k < kWaves; ++k)
-        r = fmaxf(r, lds[k]);
-    __syncthreads();
-    return r;
+    for (int k = 1; k < kWaves; ++k) {
+        a = fmaxf(a, lds[k]);
+        b = fmaxf(b, lds[kWaves + k]);
+    }
 }
 
-__device__ __forceinline__ float block_sum(float v, float *lds)
+__device__ __forceinline__ void block_sum3(float &a, float &b, float &c, float *lds)
 {
-    const float w = wave_sum(v);
-    if ((threadIdx.x & 63) == 0)
-        lds[threadIdx.x >> 6] = w;
+    const float wa = wave_sum(a), wb = wave_sum(b), wc = wave_sum(c);
+    if ((threadIdx.x & 63) == 0) {
+        lds[threadIdx.x >> 6] = wa;
+        lds[kWaves + (threadIdx.x >> 6)] = wb;
+        lds[2 * kWaves + (threadIdx.x >> 6)] = wc;
+    }
     __syncthreads();
-    float r = lds[0];
+    a = lds[0];
+    b = lds[kWaves];
+    c = lds[2 * kWaves];
 #pragma unroll
-    for (int k = 1; k < kWaves; ++k)
-        r += lds[k];
-    __syncthreads();
-    return r;
+    for (int k = 1; k < kWaves; ++k) {
+        a += lds[k];
+        b += lds[kWaves + k];
+        c += lds[2 * kWaves + k];
+    }
 }
 
 // Optional per-token reward shaping done by the lane that writes the row's
@@ -159,11 +173,39 @@ __global__ __launch_bounds__(kThreads) void logprob_kl_kernel(
     float *__restrict__ logp_out, float *__restrict__ kl_out, int64_t n_rows, int vocab, int64_t stride,
     Shaping sh)
 {
-    __shared__ float lds[kWaves];
+    __shared__ float lds_max[2 * kWaves], lds_sum[3 * kWaves];
     const int64_t row = (int64_t)blockIdx.y * kRowSlab + blockIdx.x;
     if (row >= n_rows)  // the last slab of a grid of more than kRowSlab rows
         return;
     const int tid = threadIdx.x;
+    constexpr int E = Logit<DT>::kPerVec;
+    constexpr int EB = (DT == RLHF_F32) ? 4 : 2;
+    const char *arow = (const char *)actor + row * stride * EB;
+    const char *rrow = (const char *)ref + row * stride * EB;
+
+    // The row's first loads go out before anything else is waited for: a workgroup
+    // owns one row, so whatever precedes its first load (the token id, its check)
+    // is time in which its share of the memory system idles.  A padded row pays
+    // for loads it does not use.
+    const int nvec = VEC ? vocab / E : 0;
+    // Rows whose byte length is not a multiple of 128 start off a 128-byte line
+    // every other row; then each wavefront's 1 KB load would straddle nine lines
+    // instead of eight.  The vectors before the first line boundary are taken
+    // by the first lanes, and the streaming loop starts on the boundary.
+    const int head = VEC ? min((int)(((128u - (uint32_t)((uintptr_t)arow & 127u)) & 127u) >> 4), nvec) : 0;
+    const uint4 *pa = (const uint4 *)arow;
+    const uint4 *pr = (const uint4 *)rrow;
+    int i = head + tid;
+    uint4 va[kUnroll], vr[kUnroll];
+    bool more = VEC && i + (kUnroll - 1) * kThreads < nvec;
+    if (more) {
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            va[u] = load16(pa + i + u * kThreads);
+            vr[u] = load16(pr + i + u * kThreads);
+        }
+    }
+
     const int tok = tokens[row];
     if (tok < 0 || tok >= vocab) {  // padded position: uniform across the block
         if (tid == 0) {
@@ -178,12 +220,8 @@ __global__ __launch_bounds__(kThreads) void logprob_kl_kernel(
         }
         return;
     }
-    constexpr int E = Logit<DT>::kPerVec;
-    constexpr int EB = (DT == RLHF_F32) ? 4 : 2;
-    const char *arow = (const char *)actor + row * stride * EB;
-    const char *rrow = (const char *)ref + row * stride * EB;
 
-    // issue the gather of the sampled token's logit before the long stream
+    // the gather of the sampled token's logit, issued before the long stream
     float a_tok = 0.f, r_tok = 0.f, terminal = 0.f;
     if (tid == 0) {
         a_tok = load_scalar<DT>(arow, tok);
@@ -195,28 +233,8 @@ __global__ __launch_bounds__(kThreads) void logprob_kl_kernel(
 
     RowSums st;
     if constexpr (VEC) {
-        const int nvec = vocab / E;
-        // Rows whose byte length is not a multiple of 128 start off a 128-byte line
-        // every other row; then each wavefront's 1 KB load would straddle nine lines
-        // instead of eight.  The vectors before the first line boundary are taken
-        // by the first lanes, and the streaming loop starts on the boundary.
-        const int head = min((int)(((128u - (uint32_t)((uintptr_t)arow & 127u)) & 127u) >> 4), nvec);
-        if (tid < head) {
-            float fa[E], fr[E];
-            unpack_vec<DT>(load16((const uint4 *)arow + tid), fa);
-            unpack_vec<DT>(load16((const uint4 *)rrow + tid), fr);
-            accumulate<E>(st, fa, fr);
-        }
-        const uint4 *pa = (const uint4 *)arow;
-        const uint4 *pr = (const uint4 *)rrow;
-        int i = head + tid;
-        for (; i + (kUnroll - 1) * kThreads < nvec; i += kUnroll * kThreads) {
-            uint4 va[kUnroll], vr[kUnroll];
-#pragma unroll
-            for (int u = 0; u < kUnroll; ++u) {
-                va[u] = load16(pa + i + u * kThreads);
-                vr[u] = load16(pr + i + u * kThreads);
-            }
+        // each batch is loaded while the one before it is still being summed
+        while (more) {
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
                 float fa[E], fr[E];
@@ -224,11 +242,26 @@ __global__ __launch_bounds__(kThreads) void logprob_kl_kernel(
                 unpack_vec<DT>(vr[u], fr);
                 accumulate<E>(st, fa, fr);
             }
+            i += kUnroll * kThreads;
+            more = i + (kUnroll - 1) * kThreads < nvec;
+            if (more) {
+#pragma unroll
+                for (int u = 0; u < kUnroll; ++u) {
+                    va[u] = load16(pa + i + u * kThreads);
+                    vr[u] = load16(pr + i + u * kThreads);
+                }
+            }
         }
         for (; i < nvec; i += kThreads) {
             float fa[E], fr[E];
             unpack_vec<DT>(load16(pa + i), fa);
             unpack_vec<DT>(load16(pr + i), fr);
+            accumulate<E>(st, fa, fr);
+        }
+        if (tid < head) {
+            float fa[E], fr[E];
+            unpack_vec<DT>(load16((const uint4 *)arow + tid), fa);
+            unpack_vec<DT>(load16((const uint4 *)rrow + tid), fr);
             accumulate<E>(st, fa, fr);
         }
         const int done = nvec * E;
@@ -238,22 +271,21 @@ __global__ __launch_bounds__(kThreads) void logprob_kl_kernel(
             accumulate<1>(st, fa, fr);
         }
     } else {
-        for (int i = tid; i < vocab; i += kThreads) {
-            float fa[1] = {load_scalar<DT>(arow, i)};
-            float fr[1] = {load_scalar<DT>(rrow, i)};
+        for (int j = tid; j < vocab; j += kThreads) {
+            float fa[1] = {load_scalar<DT>(arow, j)};
+            float fr[1] = {load_scalar<DT>(rrow, j)};
             accumulate<1>(st, fa, fr);
         }
     }
 
     // Merge the lanes.  Actor and reference go through the same sequence of
     // operations, so identical rows give identical lse values and KL == 0 exactly.
-    const float a_ref2 = block_max(st.a_ref2, lds);
-    const float r_ref2 = block_max(st.r_ref2, lds);
+    float a_ref2 = st.a_ref2, r_ref2 = st.r_ref2;
+    block_max2(a_ref2, r_ref2, lds_max);
     const float sca = fast_exp2(st.a_ref2 - a_ref2);
     const float scr = fast_exp2(st.r_ref2 - r_ref2);
-    const float sa = block_sum(st.sa * sca, lds);
-    const float sr = block_sum(st.sr * scr, lds);
-    const float t = block_sum(st.t * sca, lds);
+    float sa = st.sa * sca, sr = st.sr * scr, t = st.t * sca;
+    block_sum3(sa, sr, t, lds_sum);
     if (tid == 0) {
         // lse_r - lse_a is formed in log2 units before the single multiply, so
         // that no fused multiply-add can see one side rounded and the other not.
