@@ -2,6 +2,8 @@
 oracle on the same seeded inputs.  Tolerances are fixed in advance:
 2e-3 max-abs on attention outputs, 1e-3 on log-probs and KL (fp32
 accumulation), bit-exact for every integer / byte result."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -1376,6 +1378,18 @@ def test_rollout_demo_runs_the_whole_path(gu, cfg_index, batch):
     assert r["arena_allocated_bytes"] <= r["arena_reserved_bytes"]
     r = rollout_demo.run(cfg_index, gen_len=2, batch=batch, verbose=False, top_k=20)     # the truncated draw
     assert r["generated"] == 2 * batch and r["mean_logp"] <= 0
+
+
+def test_a_process_may_record_its_first_decode_attention_call_into_a_graph(gu):
+    """The header lets the compute calls be recorded into a HIP graph with no eager
+    call before.  Checked where it can be: in a fresh process
+    (tests/cold_capture_check.py) whose first decode-attention call happens
+    during capture; its replays must equal a later eager call bit for bit."""
+    import subprocess
+    import sys
+    script = os.path.join(os.path.dirname(os.path.abspath(__file__)), "cold_capture_check.py")
+    res = subprocess.run([sys.executable, script], capture_output=True, text=True, timeout=240)
+    assert res.returncode == 0 and "OK" in res.stdout, (res.stdout + res.stderr)[-3000:]
 
 
 def test_compute_entry_points_replay_from_a_hip_graph(gu):
