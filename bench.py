@@ -466,7 +466,8 @@ def main():
         "roofline": {"kernel": "logprob_kl_kernel", "bound": "hbm", "achieved": round(m["logp_gbps"], 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(m["logp_gbps"] / HBM_PEAK_GBPS, 4),
                      "traffic": measured_traffic("logprob_kl", cfg.index)},
-        "roofline_decode_attn": {"kernel": attn_kernel + " (one launch: the wavefront that completes a unit merges it)",
+        "roofline_decode_attn": {"kernel": attn_kernel + (" (one launch: the wavefront that completes a unit merges it)"
+                                                          if cfg.n_q_heads == cfg.n_kv_heads else "+attn_merge_kernel"),
                                  "bound": "hbm",
                                  "achieved": round(m["attn_gbps"], 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                                  "frac": round(m["attn_gbps"] / HBM_PEAK_GBPS, 4),

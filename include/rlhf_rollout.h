@@ -242,18 +242,18 @@ int rlhf_kv_arena_gather(const rlhf_kv_arena *arena, int32_t seq_id, int32_t sta
  * 8192 per call, nor batch * n_q_heads 2^26 - 4 (RLHF_ERR_UNSUPPORTED; split
  * larger batches).
  *
- * Launches.  The call is one kernel launch when it can be: the wavefront that
- * completes a (sequence, head) unit merges the unit's split partials itself.
- * That needs one arrival counter per unit, which cannot live in a workspace
- * whose contents are undefined; the counters are device memory of the
- * library's (zero when loaded, and every call leaves them zero), one set for
- * each of the first 8 streams that call on a device, since calls on one stream
- * never overlap.  The call falls back to two launches (split kernel, merge
- * kernel; no state at all) while its stream is being captured into a graph, on
- * further streams, above 32768 units per call (a unit is a (sequence, KV head)
- * pair, or (sequence, query head) when the two counts are equal), and when the
- * units are so few that one wavefront would have to merge dozens of partials.
- * Both forms give the same results up to fp32 summation order; each is
+ * Launches.  With one query head per KV head the call is one kernel launch
+ * when it can be: the wavefront that completes a (sequence, head) unit merges
+ * the unit's split partials itself.  That needs one arrival counter per unit,
+ * which cannot live in a workspace whose contents are undefined; the counters
+ * are device memory of the library's (zero when loaded, and every call leaves
+ * them zero), one set for each of the first 8 streams that call on a device,
+ * since calls on one stream never overlap.  The call takes two launches (split
+ * kernel, merge kernel; no state at all) with grouped-query heads (where the
+ * merge kernel's wavefront per query head is faster), while its stream is
+ * being captured into a graph, on further streams, above 32768 (sequence, head)
+ * units per call, and when the units are so few that one wavefront would have
+ * to merge dozens of partials.  Both forms give bit-identical results; each is
  * deterministic for given inputs, and neither depends on which physical pages
  * a sequence owns.  A stream destroyed while a call on it is still running
  * must not be replaced by a new stream that calls at once (the new one could

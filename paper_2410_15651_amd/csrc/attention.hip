@@ -27,9 +27,10 @@
 // every call), one set per stream that calls, because two calls running at once
 // must not share them.  Two launches: a second kernel with one wavefront per
 // (sequence, query head) does the merge; this needs no state at all and is what
-// runs while the stream is being captured into a graph, for streams beyond the
-// table, for calls with more units than a counter set holds, and for calls with
-// so few units that one wavefront would merge hundreds of partials.
+// runs for grouped-query heads, while the stream is being captured into a
+// graph, for streams beyond the table, for calls with more units than a counter
+// set holds, and for calls with so few units that one wavefront would merge
+// dozens of partials.
 //
 // Partial slots need no bookkeeping: along the axis both the wavefront index w
 // and the unit index u only grow, and each new segment raises w + u by at least
@@ -92,11 +93,13 @@ constexpr int kWavesPerCuGqa = 4;
 constexpr int kStreamSets = 8;
 constexpr int kCounterSets = kStreamSets + 1;
 constexpr int kMaxFusedUnits = 1 << 15;
-// The one-launch path is taken while a wavefront merges at most about this many
-// partials per unit on average (ranges / units); above that the merge kernel's
-// wavefront per query head is the better tool.
-constexpr int kFusedMaxAvgPartialsMha = 32;
-constexpr int kFusedMaxAvgPartialsGqa = 8;
+// The one-launch path is for one query head per KV head, while a wavefront merges
+// at most about this many partials per unit on average (ranges / units).  Above
+// that, and for grouped heads (a unit's partial is up to sixteen rows, and one
+// wavefront merging them all loses to the merge kernel's wavefront per query
+// head: measured 27 against 26 us, 21 against 17 us on small calls, even at 262 us),
+// the merge kernel is the better tool.
+constexpr int kFusedMaxAvgPartials = 8;
 
 // Device memory owned by the library.  Host code never uses these names as
 // addresses: the per-device addresses come from hipGetSymbolAddress.
@@ -549,7 +552,6 @@ __global__ __launch_bounds__(kThreads) void attn_stream_gqa_kernel(
     const uint16_t *__restrict__ q, const uint16_t *__restrict__ k_arena,
     const uint16_t *__restrict__ v_arena, const int32_t *__restrict__ page_table,
     const int32_t *__restrict__ seq_lens, int32_t *__restrict__ prefix_out, float *__restrict__ partials,
-    unsigned int *__restrict__ arrivals, void *__restrict__ out, int out_f32,
     int batch, int n_q_heads, int n_kv_heads, int mpps, int max_len, int n_waves, float scale_log2)
 {
     constexpr int NL = D / 32;
@@ -557,8 +559,7 @@ __global__ __launch_bounds__(kThreads) void attn_stream_gqa_kernel(
     int *s_prefix = s_dyn;
     int *s_scan = s_dyn + batch + 1;
     const int total_pages = build_prefix(seq_lens, batch, max_len, s_prefix, s_scan);
-    const bool one_launch = arrivals != nullptr;
-    if (blockIdx.x == 0 && !one_launch)
+    if (blockIdx.x == 0)  // the merge kernel's copy of the prefix
         for (int i = threadIdx.x; i <= batch; i += kThreads)
             prefix_out[i] = s_prefix[i];
 
@@ -570,8 +571,6 @@ __global__ __launch_bounds__(kThreads) void attn_stream_gqa_kernel(
     const int w = __builtin_amdgcn_readfirstlane(blockIdx.x * kWgWaves + (threadIdx.x >> 6));
     const int64_t total = (int64_t)total_pages * units;
     const int n_ranges = (int)min((int64_t)n_waves, total);  // never more wavefronts than steps
-    if (one_launch)
-        zero_empty_rows(s_prefix, out, out_f32, batch, n_q_heads, D, w, n_waves, lane);
     if (w >= n_ranges)
         return;
     const int64_t s0 = range_begin(w, total, n_ranges), s1 = range_begin(w + 1, total, n_ranges);
@@ -664,101 +663,26 @@ __global__ __launch_bounds__(kThreads) void attn_stream_gqa_kernel(
         }
     };
     // o[i][e][j] is row 4g+j of its tile, i.e. dim 32i + 2(4g+j) + e, for head c.
-    // Ends the segment as in attn_stream_kernel; a unit's partial is one row per
-    // query head of the unit, and the merging wavefront handles all heads at once
-    // (lane (g, c) keeps the 2 * 4 * NL dims it owns in the accumulator layout).
-    int seg_page0 = cur.page;
+    // A unit's partial is one row per query head of the unit, at slot w + unit.
     auto flush = [&](const Cursor &cu) {
         float l_all = lsum + __shfl_xor(lsum, 16);
         l_all += __shfl_xor(l_all, 32);
-        const int64_t unit = (int64_t)cu.b * units + cu.h;
-        const int hkv = cu.h / n_qb, qb = cu.h - hkv * n_qb;
-        const int64_t out_row = ((int64_t)cu.b * n_q_heads + hkv * group + qb * 16 + c) * D;
-        if (one_launch && seg_page0 == 0 && cu.page == cu.np - 1) {
-            if (c < n_heads_here) {
-                const float inv = 1.0f / l_all;
+        if (c < n_heads_here) {
+            float *dst = partials +
+                         (((int64_t)w + (int64_t)cu.b * units + cu.h) * rows_per_unit + c) * (D + 2);
 #pragma unroll
-                for (int i = 0; i < NL; ++i)
+            for (int i = 0; i < NL; ++i)
 #pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        store_pair<DT>(out, out_row + 32 * i + 2 * (4 * g + j), o[i][0][j] * inv,
-                                       o[i][1][j] * inv, out_f32 != 0);
-            }
-        } else {
-            if (c < n_heads_here) {
-                float *dst = partials + (((int64_t)w + unit) * rows_per_unit + c) * (D + 2);
-#pragma unroll
-                for (int i = 0; i < NL; ++i)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        store_pair_device(dst + 32 * i + 2 * (4 * g + j), o[i][0][j], o[i][1][j]);
-                if (g == 0)
-                    store_pair_device(dst + D, m, l_all);
-            }
-            if (one_launch) {
-                const int64_t first = (int64_t)units * s_prefix[cu.b] + (int64_t)cu.h * cu.np;
-                const int64_t w_first = seg_page0 == 0 ? w : range_owner(first, total, n_ranges);
-                const int64_t w_last = cu.page == cu.np - 1 ? w : range_owner(first + cu.np - 1, total, n_ranges);
-                const int count = (int)(w_last - w_first + 1);
-                if (arrive_last(arrivals + unit, count, lane) && c < n_heads_here) {
-                    // partials w_first .. w_last of this unit, always in that order, two per round trip
-                    const int64_t row_stride = (int64_t)rows_per_unit * (D + 2);
-                    const float *src = partials + ((w_first + unit) * rows_per_unit + c) * (D + 2);
-                    float M = -INFINITY, L = 0.f;
-                    float2 a[NL][4];
-#pragma unroll
-                    for (int i = 0; i < NL; ++i)
-#pragma unroll
-                        for (int j = 0; j < 4; ++j)
-                            a[i][j] = make_float2(0.f, 0.f);
-                    for (int i0 = 0; i0 < count; i0 += 2) {
-                        const float *r0 = src + (int64_t)i0 * row_stride;
-                        const float *r1 = src + (int64_t)min(i0 + 1, count - 1) * row_stride;
-                        const float2 ml0 = load_pair_device(r0 + D), ml1 = load_pair_device(r1 + D);
-                        float2 v0[NL][4], v1[NL][4];
-#pragma unroll
-                        for (int i = 0; i < NL; ++i)
-#pragma unroll
-                            for (int j = 0; j < 4; ++j) {
-                                v0[i][j] = load_pair_device(r0 + 32 * i + 2 * (4 * g + j));
-                                v1[i][j] = load_pair_device(r1 + 32 * i + 2 * (4 * g + j));
-                            }
-                        float alpha, e;
-                        merge_step(M, L, ml0.x, ml0.y, alpha, e);
-#pragma unroll
-                        for (int i = 0; i < NL; ++i)
-#pragma unroll
-                            for (int j = 0; j < 4; ++j) {
-                                a[i][j].x = fmaf(a[i][j].x, alpha, e * v0[i][j].x);
-                                a[i][j].y = fmaf(a[i][j].y, alpha, e * v0[i][j].y);
-                            }
-                        if (i0 + 1 < count) {  // otherwise r1 was the last row again, unused
-                            merge_step(M, L, ml1.x, ml1.y, alpha, e);
-#pragma unroll
-                            for (int i = 0; i < NL; ++i)
-#pragma unroll
-                                for (int j = 0; j < 4; ++j) {
-                                    a[i][j].x = fmaf(a[i][j].x, alpha, e * v1[i][j].x);
-                                    a[i][j].y = fmaf(a[i][j].y, alpha, e * v1[i][j].y);
-                                }
-                        }
-                    }
-                    const float inv = 1.0f / L;
-#pragma unroll
-                    for (int i = 0; i < NL; ++i)
-#pragma unroll
-                        for (int j = 0; j < 4; ++j)
-                            store_pair<DT>(out, out_row + 32 * i + 2 * (4 * g + j), a[i][j].x * inv,
-                                           a[i][j].y * inv, out_f32 != 0);
-                }
-            }
+                for (int j = 0; j < 4; ++j)
+                    *(float2 *)(dst + 32 * i + 2 * (4 * g + j)) = make_float2(o[i][0][j], o[i][1][j]);
+            if (g == 0)
+                *(float2 *)(dst + D) = make_float2(m, l_all);
         }
         m = -INFINITY;
         lsum = 0.f;
 #pragma unroll
         for (int i = 0; i < NL; ++i)
             o[i][0] = o[i][1] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-        seg_page0 = 0;
     };
 
     // one page ahead, last step peeled (see attn_stream_kernel)
@@ -977,8 +901,7 @@ int launch(const rlhf_attn_params &p, const Shape &sh, const void *q, const void
             workspace = d->scratch;
         // ranges the kernel will cut the axis into, at most: wavefronts, or page steps if fewer
         const int64_t ranges = std::min<int64_t>(n_waves, n_units * ((sh.max_len + kPage - 1) / kPage));
-        const int avg_cap = sh.group == 1 ? kFusedMaxAvgPartialsMha : kFusedMaxAvgPartialsGqa;
-        if (!capturing && n_units <= kMaxFusedUnits && ranges <= avg_cap * n_units) {
+        if (!capturing && sh.group == 1 && n_units <= kMaxFusedUnits && ranges <= kFusedMaxAvgPartials * n_units) {
             const int set = where == Scratch::Library ? kStreamSets : counter_set_of(d, s);
             if (set >= 0)
                 arrivals = d->arrivals + (size_t)set * kMaxFusedUnits;
@@ -997,9 +920,8 @@ int launch(const rlhf_attn_params &p, const Shape &sh, const void *q, const void
     } else {
         hipLaunchKernelGGL((attn_stream_gqa_kernel<DT, D>), dim3(n_waves / kWgWaves), dim3(kThreads), lds, s,
                            (const uint16_t *)q, (const uint16_t *)k_arena, (const uint16_t *)v_arena,
-                           page_table, seq_lens, prefix, partials, arrivals, out, out_f32, p.batch,
-                           p.n_q_heads, p.n_kv_heads, p.max_pages_per_seq, sh.max_len, n_waves,
-                           scale * kLog2e);
+                           page_table, seq_lens, prefix, partials, p.batch, p.n_q_heads, p.n_kv_heads,
+                           p.max_pages_per_seq, sh.max_len, n_waves, scale * kLog2e);
         RLHF_LAUNCH_CHECK("attn_stream_gqa_kernel");
     }
     if (arrivals != nullptr)
