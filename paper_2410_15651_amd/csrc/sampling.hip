@@ -335,19 +335,25 @@ __device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v)
 // consecutive entries x[0..cnt) starting at index v0 (a whole 16-byte vector,
 // or one entry).  Loads go out U at a time before the first is used: a row is a
 // few loads per lane, and their latency, not their number, is what a pass costs.
+// The vectors land in the caller's u[]: a row of at most U * 1024 vectors (every
+// vocabulary the paper's models have) is one such batch, so after the first pass
+// it sits in registers, and a later pass with `reuse` set reads nothing at all.
 template <int DT, bool VEC, int U, class F>
-__device__ __forceinline__ void row_foreach(const char *base, int vocab, int tid, F &&f)
+__device__ __forceinline__ void row_foreach(const char *base, int vocab, int tid, uint4 (&u)[U], bool reuse,
+                                            F &&f)
 {
     if constexpr (VEC) {
         constexpr int E = (DT == RLHF_F32) ? 4 : 8;
         const int nvec = vocab / E;
         const uint4 *p = (const uint4 *)base;
+        const bool keep = reuse && nvec <= U * kTopkThreads;  // u[] still holds the whole row
         for (int i0 = tid; i0 < nvec; i0 += U * kTopkThreads) {
-            uint4 u[U];  // the row is read several times: ordinary loads, it stays in L2
+            if (!keep) {  // ordinary loads: a row too long for the registers is read again from L2
 #pragma unroll
-            for (int j = 0; j < U; ++j)
-                if (i0 + j * kTopkThreads < nvec)
-                    u[j] = p[i0 + j * kTopkThreads];
+                for (int j = 0; j < U; ++j)
+                    if (i0 + j * kTopkThreads < nvec)
+                        u[j] = p[i0 + j * kTopkThreads];
+            }
 #pragma unroll
             for (int j = 0; j < U; ++j) {
                 const int i = i0 + j * kTopkThreads;
@@ -421,9 +427,11 @@ __global__ __launch_bounds__(kTopkThreads) void sample_topk_kernel(
 {
     __shared__ uint32_t s_key[kTopkCap];
     __shared__ int s_idx[kTopkCap];
+    __shared__ uint32_t s_max[kTopkThreads];  // the lanes' maxima: apart from the list, which a fast
+                                              // wavefront may start to fill while a slow one still reads these
     __shared__ uint32_t s_top[kTopkWaves], s_low[kTopkWaves], s_cnt[2][kTopkWaves], s_i[kTopkWaves];
-    __shared__ float s_f[kTopkWaves], s_r[kTopkWaves], s_s[kTopkWaves];
-    __shared__ int s_fill;
+    __shared__ float s_f[kTopkWaves], s_r[kTopkWaves], s_s[kTopkWaves], s_y[kTopkWaves];
+    __shared__ int s_fill[3];  // the sweeps' candidate counters, one per round in rotation
     const int64_t row64 = (int64_t)blockIdx.y * kRowSlab + blockIdx.x;
     if (row64 >= n_rows)  // the last slab of a grid of more than kRowSlab rows
         return;
@@ -447,13 +455,16 @@ __global__ __launch_bounds__(kTopkThreads) void sample_topk_kernel(
     const uint32_t k = (uint32_t)min(top_k, vocab);
     const int owners = VEC ? min(kTopkThreads, vocab / (16 / EB)) : min(kTopkThreads, vocab);  // lanes 0 .. owners-1 have entries
     float mine_f = -INFINITY;
-    row_foreach<DT, VEC, 8>(base, vocab, tid, [&](const float *x, int cnt, int) {
+    uint4 rowv[16];  // the lane's vectors of the row, kept for the sweeps when the row fits
+    row_foreach<DT, VEC, 16>(base, vocab, tid, rowv, false, [&](const float *x, int cnt, int) {
 #pragma unroll
         for (int j = 0; j < cnt; ++j)
             mine_f = fmaxf(mine_f, x[j]);
     });
     const uint32_t mine = skey(mine_f);
-    s_key[tid] = mine;
+    s_max[tid] = mine;
+    if (tid < 2)
+        s_fill[tid] = 0;  // rounds 0 and 1; every round clears the counter of the round after it
     {
         const uint32_t hi_w = wave_max_u32(mine), lo_w = wave_min_u32(tid < owners ? mine : 0xffffffffu);
         if (lane == 0) {
@@ -475,7 +486,7 @@ __global__ __launch_bounds__(kTopkThreads) void sample_topk_kernel(
     // Lane maxima at or above a threshold undercount the row's entries there, the
     // more so the closer their number is to all 1024: no slack then.
     uint32_t c_lo = kTopkThreads, slack = min(max(k >> 3, 16u), k < 896u ? 896u - k : 0u);
-    int n_list = kTopkThreads, parity = 0;
+    int n_list = kTopkThreads;
     bool listed = true;
     const bool count_only = k > (uint32_t)kTopkCap;  // the candidates can never fit the list
     // phase 0 (k <= 1024 only): the search runs on the lane maxima and leaves in
@@ -492,13 +503,16 @@ __global__ __launch_bounds__(kTopkThreads) void sample_topk_kernel(
             // doublings and is cut off at 140 rounds; bisection halves the bracket
             // every round.
             for (int round = 0;; ++round) {
-                // one sweep: count the entries at or above t, keep the first kTopkCap of them
+                // one sweep: count the entries at or above t, keep the first kTopkCap of them.
+                // This round's counter was cleared two barriers ago; the next round's is
+                // cleared now (its last readers passed the barrier that ended the round
+                // before this one), so a round costs one barrier.
+                int *const fill = &s_fill[round % 3];
                 if (tid == 0)
-                    s_fill = 0;
-                __syncthreads();
+                    s_fill[(round + 1) % 3] = 0;
                 const float tv = threshold_value(t);
                 uint32_t local = 0;
-                row_foreach<DT, VEC, 8>(base, vocab, tid, [&](const float *x, int cnt, int v0) {
+                row_foreach<DT, VEC, 16>(base, vocab, tid, rowv, true, [&](const float *x, int cnt, int v0) {
                     if (count_only) {
 #pragma unroll
                         for (int j = 0; j < cnt; ++j)
@@ -531,7 +545,7 @@ __global__ __launch_bounds__(kTopkThreads) void sample_topk_kernel(
                     int first = 0;
                     if (__builtin_amdgcn_mbcnt_hi((uint32_t)(active >> 32),
                                                   __builtin_amdgcn_mbcnt_lo((uint32_t)active, 0u)) == 0)
-                        first = atomicAdd(&s_fill, (int)total);
+                        first = atomicAdd(fill, (int)total);
                     int at = __builtin_amdgcn_readfirstlane(first) + (int)before;
                     while (mask) {
                         const int e = __ffs(mask) - 1;
@@ -550,11 +564,10 @@ __global__ __launch_bounds__(kTopkThreads) void sample_topk_kernel(
                 if (count_only) {
                     local = wave_sum_u32(local);
                     if (lane == 0)
-                        atomicAdd(&s_fill, (int)local);
+                        atomicAdd(fill, (int)local);
                 }
                 __syncthreads();
-                const uint32_t c = (uint32_t)s_fill;
-                __syncthreads();
+                const uint32_t c = (uint32_t)*fill;
                 if (c >= k) {
                     lo = t;
                     c_lo = c;
@@ -590,45 +603,69 @@ __global__ __launch_bounds__(kTopkThreads) void sample_topk_kernel(
                 break;
             slack = 0;
         }
-        // Narrows [lo, hi) on the n_list keys in s_key until count(>= lo), kept in
-        // c_lo, is within `slack` of k or the bracket is one key wide.  Wavefront w
-        // counts the keys at or above a threshold of its own, the bracket cut in
-        // seventeen; the first wavefront's threshold lies strictly inside the
-        // bracket whenever it is two keys wide or more, so every round shrinks it.
-        // A round's counts go to the half of s_cnt the previous round did not use:
-        // one barrier per round.
-        uint32_t held[16];  // the first 1024 keys, the same in every wavefront
+        // Narrows [lo, hi) on the n_list keys until count(>= lo), kept in c_lo, is
+        // within `slack` of k or the bracket is one key wide.  Every wavefront holds
+        // the first 1024 keys in registers (sixteen per lane).  Up to 1024 keys, each
+        // wavefront runs the whole bisection on its own: a probe is sixteen compares
+        // and scalar population counts, so the search needs no LDS traffic and no
+        // barrier, and all wavefronts arrive at the same bracket.
+        const uint32_t *keys = phase == 0 ? s_max : s_key;
+        uint32_t held[16];
 #pragma unroll
         for (int j = 0; j < 16; ++j)
-            held[j] = (lane + 64 * j < n_list) ? s_key[lane + 64 * j] : 0u;  // thresholds are above lo >= 0
-        while (hi - lo > 1 && c_lo > k + slack) {
-            const uint32_t span = hi - lo, part = span / (kTopkWaves + 1), rest = span - part * (kTopkWaves + 1);
-            const uint32_t my_t = lo + part * (uint32_t)(wv + 1) + min((uint32_t)(wv + 1), rest);
-            uint32_t c = 0;
+            held[j] = (lane + 64 * j < n_list) ? keys[lane + 64 * j] : 0u;  // thresholds are above lo >= 0
+        if (n_list <= kTopkThreads) {
+            while (hi - lo > 1 && c_lo > k + slack) {
+                const uint32_t t = lo + (hi - lo) / 2;  // strictly inside the bracket
+                uint32_t c = 0;
 #pragma unroll
-            for (int j = 0; j < 16; ++j)
-                c += (uint32_t)__popcll(__ballot(held[j] >= my_t));
-            for (int i = 1024 + lane; i < n_list; i += 64)
-                c += (uint32_t)__popcll(__ballot(s_key[i] >= my_t));
-            if (lane == 0)
-                s_cnt[parity][wv] = c;
-            __syncthreads();
-            uint32_t nlo = lo, nhi = hi, nc = c_lo;
-#pragma unroll
-            for (int w = 0; w < kTopkWaves; ++w) {  // thresholds rise with w, counts fall
-                const uint32_t tw = lo + part * (uint32_t)(w + 1) + min((uint32_t)(w + 1), rest);
-                const uint32_t cw = s_cnt[parity][w];
-                if (cw >= k) {
-                    nlo = tw;
-                    nc = cw;
+                for (int j = 0; j < 16; ++j)
+                    c += (uint32_t)__popcll(__ballot(held[j] >= t));
+                if (c >= k) {
+                    lo = t;
+                    c_lo = c;
                 } else {
-                    nhi = min(nhi, tw);
+                    hi = t;
                 }
             }
-            lo = nlo;
-            hi = nhi;
-            c_lo = nc;
-            parity ^= 1;
+        } else {
+            // A list of more than 1024 keys (k near or above 1024): the part beyond the
+            // registers is read from LDS at every probe, so the wavefronts share the
+            // work instead -- wavefront w counts the keys at or above a threshold of its
+            // own, the bracket cut in seventeen; the first wavefront's threshold lies
+            // strictly inside the bracket whenever it is two keys wide or more, so every
+            // round shrinks it.  A round's counts go to the half of s_cnt the previous
+            // round did not use: one barrier per round.
+            int parity = 0;
+            while (hi - lo > 1 && c_lo > k + slack) {
+                const uint32_t span = hi - lo, part = span / (kTopkWaves + 1), rest = span - part * (kTopkWaves + 1);
+                const uint32_t my_t = lo + part * (uint32_t)(wv + 1) + min((uint32_t)(wv + 1), rest);
+                uint32_t c = 0;
+#pragma unroll
+                for (int j = 0; j < 16; ++j)
+                    c += (uint32_t)__popcll(__ballot(held[j] >= my_t));
+                for (int i = 1024 + lane; i < n_list; i += 64)
+                    c += (uint32_t)__popcll(__ballot(s_key[i] >= my_t));  // complete in lane 0, which goes round longest
+                if (lane == 0)
+                    s_cnt[parity][wv] = c;
+                __syncthreads();
+                uint32_t nlo = lo, nhi = hi, nc = c_lo;
+#pragma unroll
+                for (int w = 0; w < kTopkWaves; ++w) {  // thresholds rise with w, counts fall
+                    const uint32_t tw = lo + part * (uint32_t)(w + 1) + min((uint32_t)(w + 1), rest);
+                    const uint32_t cw = s_cnt[parity][w];
+                    if (cw >= k) {
+                        nlo = tw;
+                        nc = cw;
+                    } else {
+                        nhi = min(nhi, tw);
+                    }
+                }
+                lo = nlo;
+                hi = nhi;
+                c_lo = nc;
+                parity ^= 1;
+            }
         }
         if (phase == 0)
             hi = top + 1;  // lo bounds tau from below; the row's bracket is open above again
@@ -645,7 +682,8 @@ __global__ __launch_bounds__(kTopkThreads) void sample_topk_kernel(
         // survivors are many: the plain draw's sweep, removed entries at -inf
         // (no weight in the sum, never the maximum)
         const float tv = threshold_value(tau);
-        row_foreach<DT, VEC, 1>(base, vocab, tid, [&](const float *x, int cnt, int v0) {
+        uint4 one[1];
+        row_foreach<DT, VEC, 1>(base, vocab, tid, one, false, [&](const float *x, int cnt, int v0) {
             if (cnt == 1) {
                 if (x[0] >= tv)
                     take1<NOISE>(st, x[0] * inv_t, v0, row, off, key);
@@ -666,7 +704,9 @@ __global__ __launch_bounds__(kTopkThreads) void sample_topk_kernel(
             }
         });
     }
-    // best score (ties to the lowest index), then the sum over the survivors
+    // best score (ties to the lowest index), then the sum over the survivors.  Each
+    // wavefront fetches the logit of its own best entry before the barrier, so that
+    // the load's latency is not paid once more after the workgroup's winner is known.
     const float zw = wave_max(st.best_z);
     const uint32_t iw = wave_min_u32(st.best_z == zw ? (uint32_t)st.best_i : (uint32_t)INT_MAX);
     const float rw = wave_max(st.ref2);
@@ -676,6 +716,7 @@ __global__ __launch_bounds__(kTopkThreads) void sample_topk_kernel(
         s_i[wv] = iw;
         s_r[wv] = rw;
         s_s[wv] = sw;
+        s_y[wv] = (logp_out && iw != (uint32_t)INT_MAX) ? load_scalar<DT>(base, (int)iw) : 0.f;
     }
     __syncthreads();
     if (tid == 0) {
@@ -687,15 +728,24 @@ __global__ __launch_bounds__(kTopkThreads) void sample_topk_kernel(
             better(z, idx, s_f[w], (int)s_i[w]);
             ref2 = fmaxf(ref2, s_r[w]);
         }
-        float sum = 0.f;
+        float sum = 0.f, y = 0.f;
+        bool have = false;
 #pragma unroll
-        for (int w = 0; w < kTopkWaves; ++w)
+        for (int w = 0; w < kTopkWaves; ++w) {
             sum += s_s[w] * fast_exp2(s_r[w] - ref2);
+            if (idx != INT_MAX && (int)s_i[w] == idx) {  // the wavefront that proposed the winner holds its logit
+                y = s_y[w];
+                have = true;
+            }
+        }
         if (idx == INT_MAX)
             idx = 0;
         tokens_out[row64] = idx;
-        if (logp_out)
-            logp_out[row64] = load_scalar<DT>(base, idx) * inv_t - (ref2 + log2f(sum)) * kLn2;
+        if (logp_out) {
+            if (!have)  // no entry was drawn from (a row without numbers): token 0
+                y = load_scalar<DT>(base, idx);
+            logp_out[row64] = y * inv_t - (ref2 + log2f(sum)) * kLn2;
+        }
     }
 }
 
