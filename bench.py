@@ -321,10 +321,13 @@ def measure(cfg, K, W, dev):
 MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f16": 2500.0}   # MI355X dense matrix-core peak
 
 
-def measure_prefill(cfg, dev, reps=5):
+def measure_prefill(cfg, dev, reps=10, warmup=5):
     """The prefill step of the same configuration (outside the timed decode
     step): every sequence's prompt is appended to an empty arena in one call and
-    its causal attention runs over the arena.  Returns times and flop counts."""
+    its causal attention runs over the arena.  `warmup` untimed passes (the pass
+    follows seconds of host-only work, after which the device takes a few passes
+    to return to its working clock), then the median of `reps` passes.  Returns
+    times and flop counts."""
     import torch
     from paper_2410_15651_amd import binding as rb
     from paper_2410_15651_amd import workloads as wl
@@ -352,7 +355,7 @@ def measure_prefill(cfg, dev, reps=5):
     ids = np.arange(cfg.batch, dtype=np.int32)
     max_q = int(lens.max())
     t_app, t_att = [], []
-    for it in range(reps + 1):
+    for it in range(warmup + reps):
         rb.rlhf_kv_arena_reset(arena)
         e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
         e[0].record()
@@ -361,14 +364,15 @@ def measure_prefill(cfg, dev, reps=5):
         rb.rlhf_prefill_attention(params, q, cu_d, max_q, k_arena, v_arena, d_table, d_lens, out)
         e[2].record()
         torch.cuda.synchronize()
-        if it:                      # the first pass is the warm-up
+        if it >= warmup:
             t_app.append(e[0].elapsed_time(e[1]) * 1e-3)
             t_att.append(e[1].elapsed_time(e[2]) * 1e-3)
     rb.rlhf_kv_arena_destroy(arena)
     L = lens.astype(np.float64)
     flops = 4.0 * cfg.head_dim * cfg.n_q_heads * float((L * (L + 1) / 2).sum())   # q.K and P.V, causal
-    return dict(rows=T, flops=flops, attn_s=float(np.mean(t_att)), append_s=float(np.mean(t_app)),
-                lens_lo=int(lens.min()), lens_hi=int(lens.max()))
+    return dict(rows=T, flops=flops, attn_s=float(np.median(t_att)), append_s=float(np.median(t_app)),
+                attn_min_max_s=(float(min(t_att)), float(max(t_att))), lens_lo=int(lens.min()),
+                lens_hi=int(lens.max()))
 
 
 def read_ceiling(dev, gib=4, reps=5):
@@ -486,6 +490,8 @@ def main():
     peak = MFMA_PEAK_TFLOPS[cfg.kv_dtype]
     result["components"].update({
         "prefill_attn_us": round(pf["attn_s"] * 1e6, 1), "prefill_attn_TFLOPs": round(tfl, 1),
+        "prefill_attn_us_min_max": [round(x * 1e6, 1) for x in pf["attn_min_max_s"]],
+        "prefill_method": "median of 10 passes after 5 warm-up passes",
         "prefill_append_us": round(pf["append_s"] * 1e6, 1), "prefill_rows": pf["rows"],
         "prefill_tokens_per_s": round(pf["rows"] / (pf["attn_s"] + pf["append_s"]), 1),
         "prefill_prompt_lengths": f"U[{max(1, cfg.len_lo // 2)},{max(1, cfg.len_hi // 2)}]"})
@@ -516,7 +522,7 @@ def main():
             o["wk"].close()
             del o
             torch.cuda.empty_cache()
-            pf = measure_prefill(c, dev, reps=3)
+            pf = measure_prefill(c, dev, reps=5, warmup=3)
             others[-1].update({"prefill_attn_us": round(pf["attn_s"] * 1e6, 1),
                                "prefill_attn_TFLOPs": round(pf["flops"] / pf["attn_s"] / 1e12, 1),
                                "prefill_append_us": round(pf["append_s"] * 1e6, 1), "prefill_rows": pf["rows"]})
