@@ -271,7 +271,7 @@ __device__ __forceinline__ void store_pair(void *out, int64_t idx, float a, floa
     if (as_f32)
         *(float2 *)((float *)out + idx) = make_float2(a, b);
     else
-        *(uint32_t *)((uint16_t *)out + idx) = (uint32_t)pack16<DT>(a) | ((uint32_t)pack16<DT>(b) << 16);
+        *(uint32_t *)((uint16_t *)out + idx) = pack16x2<DT>(a, b);
 }
 
 // Log-sum-exp merge of a unit's partials, one partial at a time in range

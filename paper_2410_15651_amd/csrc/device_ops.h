@@ -56,16 +56,13 @@ __device__ __forceinline__ float load_scalar(const void *base, int64_t idx)
     }
 }
 
-// fp32 -> 16-bit storage, round to nearest even.
+// fp32 -> 16-bit storage, round to nearest even (one conversion instruction, no branch: bf16 has its
+// own on this device; NaN stays NaN, quiet).
 template <int DT>
 __device__ __forceinline__ uint16_t pack16(float x)
 {
     if constexpr (DT == RLHF_BF16) {
-        uint32_t u = __float_as_uint(x);
-        if ((u & 0x7fffffffu) > 0x7f800000u)
-            return (uint16_t)((u >> 16) | 0x40);  // quiet NaN
-        u += 0x7fffu + ((u >> 16) & 1u);
-        return (uint16_t)(u >> 16);
+        return __builtin_bit_cast(uint16_t, (__bf16)x);  // v_cvt_pk_bf16_f32
     } else {
         // The value is rounded to fp32 first and to fp16 second, always: the empty
         // statement keeps the compiler from folding the caller's last multiply into a
@@ -74,6 +71,21 @@ __device__ __forceinline__ uint16_t pack16(float x)
         asm volatile("" : "+v"(x));
         _Float16 h = (_Float16)x;  // v_cvt_f16_f32, RNE
         return __builtin_bit_cast(uint16_t, h);
+    }
+}
+
+// Two fp32 -> two 16-bit values in one word, `first` in the low half, with one packed conversion.
+template <int DT>
+__device__ __forceinline__ uint32_t pack16x2(float first, float second)
+{
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+    if constexpr (DT == RLHF_BF16) {
+        const f32x2_t v = {first, second};
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));  // v_cvt_pk_bf16_f32
+    } else {
+        asm volatile("" : "+v"(first), "+v"(second));  // see pack16
+        const f32x2_t v = {first, second};
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2_t));  // v_cvt_pk_f16_f32
     }
 }
 

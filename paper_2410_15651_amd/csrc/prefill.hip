@@ -110,7 +110,16 @@ __global__ __launch_bounds__(WAVES * 64) void prefill_attn_kernel(
     constexpr int kItems = kBlockBytes / 8;    // 16-byte copy items of K (two pages) = of V
     constexpr int kThreads = WAVES * 64;
     constexpr int kCopies = (kItems + kThreads - 1) / kThreads;
-    __shared__ __attribute__((aligned(16))) unsigned char stage[2][kStageBytes];
+    // One LDS block: the two K/V stages first (their addresses then fit the 16-bit offset field of
+    // the LDS instructions), then a per-wavefront exchange tile (32 rows of up to 256 bytes) for the
+    // output: rows leave through it, so that global memory sees whole rows (full cache lines) per
+    // store instruction although the accumulators hold the matrix layout (a lane: four dims of one
+    // row per register quad).  The 16-byte chunks of a row are XOR-swizzled with the row number to
+    // spread both access patterns over the banks.
+    constexpr int kXchgRow = 256;
+    constexpr int kXchgBytes = kTileRows * kXchgRow;
+    __shared__ __attribute__((aligned(16))) unsigned char lds[2 * kStageBytes + WAVES * kXchgBytes];
+    unsigned char (*stage)[kStageBytes] = reinterpret_cast<unsigned char (*)[kStageBytes]>(lds);
 
     // workgroup -> (unit, position block): units round-robin over the XCDs, the
     // blocks of a unit consecutive on its XCD, last block first
@@ -148,7 +157,6 @@ __global__ __launch_bounds__(WAVES * 64) void prefill_attn_kernel(
     const int r = min(r_raw, rows_wg - 1);
     const int il = r / group, hg = r - il * group;
     const int i_row = min(i0 + il, n_b - 1);
-    const bool valid = active && r_raw < rows_wg && i0 + il < n_b;
     const int pos = first + i_row;
     const int64_t row_off = ((int64_t)(q0 + i_row) * n_q_heads + hkv * group + hg) * D;
     uint4 qr[NC];
@@ -354,24 +362,54 @@ __global__ __launch_bounds__(WAVES * 64) void prefill_attn_kernel(
             advance(s + 1, set_b, set_a, std::true_type{});
     }
 
-    // o[k][r] is dim 32k + 8*(r/4) + 4h + r%4 of row c
+    // o[k][r] is dim 32k + 8*(r/4) + 4h + r%4 of row c.  The tile goes to the exchange buffer row by
+    // row (normalised, in the output type) and leaves it as whole rows: 16 bytes per lane, a row's
+    // bytes side by side in one instruction.  Everything the stores need is derived here from the
+    // lane number again, so that none of it occupies a register during the steps above.
     const float l_all = l_part + __shfl_xor(l_part, 32);
-    if (valid) {
-        const float inv = 1.0f / l_all;
+    const float inv = 1.0f / l_all;
+    int ln = threadIdx.x & 63;
+    asm volatile("" : "+v"(ln));
+    const int c2 = ln & 31, h2 = ln >> 5;
+    constexpr int OSZ = ODT == RLHF_F32 ? 4 : 2;
+    constexpr int ORB = D * OSZ < kXchgRow ? D * OSZ : kXchgRow;  // row bytes per pass
+    constexpr int NP = D * OSZ / ORB;                              // passes
+    constexpr int KP = ND / NP;                                    // 32-dim tiles per pass
+    constexpr int OCH = ORB / 16, ORPI = 64 / OCH, ON = kTileRows / ORPI;
+    const int och = ln % OCH, osub = ln / OCH;
+    const float inv_group = 1.0f / (float)group;
+    unsigned char *mine = lds + 2 * kStageBytes + wv * kXchgBytes;
 #pragma unroll
-        for (int k = 0; k < ND; ++k)
+    for (int ps = 0; ps < NP; ++ps) {
+#pragma unroll
+        for (int kk = 0; kk < KP; ++kk) {
+            const int k = ps * KP + kk;
 #pragma unroll
             for (int qd = 0; qd < 4; ++qd) {
-                const int64_t idx = row_off + 32 * k + 8 * qd + 4 * h;
                 const float x0 = o[k][4 * qd] * inv, x1 = o[k][4 * qd + 1] * inv, x2 = o[k][4 * qd + 2] * inv,
                             x3 = o[k][4 * qd + 3] * inv;
+                const int off = (32 * kk + 8 * qd + 4 * h2) * OSZ;  // byte offset in the pass's row part
+                unsigned char *dst = mine + c2 * ORB + (((off >> 4) ^ (c2 % OCH)) << 4) + (off & 15);
                 if constexpr (ODT == RLHF_F32)
-                    *(float4 *)((float *)out + idx) = make_float4(x0, x1, x2, x3);
+                    *(float4 *)dst = make_float4(x0, x1, x2, x3);
                 else
-                    *(uint2 *)((uint16_t *)out + idx) =
-                        make_uint2((uint32_t)pack16<ODT>(x0) | ((uint32_t)pack16<ODT>(x1) << 16),
-                                   (uint32_t)pack16<ODT>(x2) | ((uint32_t)pack16<ODT>(x3) << 16));
+                    *(uint2 *)dst = make_uint2(pack16x2<ODT>(x0, x1), pack16x2<ODT>(x2, x3));
             }
+        }
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int t = 0; t < ON; ++t) {
+            const int j = ORPI * t + osub;
+            const int rr = r_first + j, rc = min(rr, rows_wg - 1);
+            // rc / group without an integer division: rc < 2^9, so the fp32 product is exact enough
+            const int ilj = (int)(((float)rc + 0.5f) * inv_group), hgj = rc - ilj * group;
+            const bool exists = active && rr < rows_wg && i0 + ilj < n_b;
+            const int64_t row = ((int64_t)(q0 + min(i0 + ilj, n_b - 1)) * n_q_heads + hkv * group + hgj) * D;
+            const uint4 w = *reinterpret_cast<const uint4 *>(mine + j * ORB + ((och ^ (j % OCH)) << 4));
+            if (exists)
+                *reinterpret_cast<uint4 *>((unsigned char *)out + row * OSZ + ps * ORB + och * 16) = w;
+        }
+        __builtin_amdgcn_wave_barrier();
     }
 }
 
