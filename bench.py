@@ -393,6 +393,33 @@ def read_ceiling(dev, gib=4, reps=5):
     return buf.numel() / (e0.elapsed_time(e1) / reps * 1e-3) / 1e9
 
 
+def matrix_ceiling(dev, iterations=20000):
+    """What a kernel of nothing but the prefill kernel's matrix instruction reaches, and the shader clock
+    the device holds meanwhile, on N(0,1) bf16 operands (the workload's K/V/q distribution) and on zeros.
+    The device lowers its clock under matrix load by an amount that depends on the operand data."""
+    import torch
+    from paper_2410_15651_amd import binding as rb
+    n_wg = torch.cuda.get_device_properties(dev).multi_processor_count
+    g = torch.Generator(device=dev)
+    g.manual_seed(20241015)
+    out = {}
+    for name, ops in (("N01", torch.randn(1 << 20, generator=g, device=dev).to(torch.bfloat16)),
+                      ("zeros", torch.zeros(1 << 20, dtype=torch.bfloat16, device=dev))):
+        ticks = torch.zeros(3, dtype=torch.int64, device=dev)
+        rb.rlhf_probe_matrix_rate(ops, 200, n_wg, ticks)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        rb.rlhf_probe_matrix_rate(ops, iterations, n_wg, ticks)
+        e1.record()
+        torch.cuda.synchronize()
+        t = ticks.cpu().tolist()
+        flops = n_wg * 12 * iterations * 8 * 32768.0
+        out[name] = {"TFLOPs": round(flops / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1),
+                     "shader_clock_MHz": round(t[1] / max(t[0], 1) * 100.0)}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -499,6 +526,11 @@ def main():
         "kernel": "prefill_attn_kernel", "bound": "mfma", "achieved": round(tfl, 1), "peak": peak,
         "unit": "TFLOP/s", "frac": round(tfl / peak, 4), "traffic": measured_traffic("prefill_attn", cfg.index),
         "flops": "4 * head_dim * q heads * sum L(L+1)/2: q.K and P.V of the causal triangle"}
+    probe = matrix_ceiling(dev)
+    result["roofline_prefill_attn"]["matrix_probe"] = {
+        **probe, "what": "a loop of 32x32x16 bf16 matrix instructions alone, three wavefronts per SIMD on every "
+                         "compute unit: the rate and the clock the device holds depend on the operand data",
+        "achieved_frac_of_probe_on_N01": round(tfl / probe["N01"]["TFLOPs"], 4)}
     torch.cuda.empty_cache()
 
     if not args.no_other_configs:

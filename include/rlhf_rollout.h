@@ -34,7 +34,7 @@
  *     (rlhf_decode_attention keeps a few counters in device memory of the
  *     library's own, one set per calling stream, zero between calls: see there.)
  *   - The compute entry points (decode and prefill attention, log-prob/KL,
- *     the draws, the read probe) allocate nothing, issue no memset or copy and
+ *     the draws, the probes) allocate nothing, issue no memset or copy and
  *     never synchronise: they may be recorded into a HIP graph on the stream
  *     they are given and replayed; a replay reads the buffers' contents of
  *     that moment.  rlhf_kv_arena_append and rlhf_kv_arena_free_seq may not
@@ -464,6 +464,22 @@ int rlhf_prefill_attention_wg(const rlhf_attn_params *params, const void *q, con
  * device's practical read ceiling to set beside the published HBM peak.  sink
  * (dev uint32 or NULL) only keeps the loads alive.  Asynchronous on stream. */
 int rlhf_probe_stream_read(const void *buffer, size_t bytes, uint32_t *sink, void *stream);
+
+/* Measurement aid, not a step of the method: n_workgroups workgroups of 768
+ * threads (three wavefronts per SIMD, as the prefill kernel runs) each take
+ * sixteen 16-byte operand registers per lane from `operands` (dev, 16-byte
+ * aligned, `bytes` >= 16, read modulo its length: bf16 values, the caller's
+ * choice) and issue iterations x 8 of the 32x32x16 bf16 matrix products the
+ * prefill kernel is made of, nothing else.  Flops = n_workgroups * 12 *
+ * iterations * 8 * 32768; the caller times the call.  ticks (dev, three
+ * uint64) receives, for workgroup 0's first wavefront, the duration of its
+ * loop in ticks of the 100 MHz wall clock ([0]) and in shader cycles ([1]):
+ * their ratio is the clock the device held, which under matrix load depends
+ * on the operand data; [2] is scratch.  Keep operand magnitudes small enough
+ * that iterations * 16 * max|a| * max|b| stays finite in fp32.  Asynchronous
+ * on stream. */
+int rlhf_probe_matrix_rate(const void *operands, size_t bytes, int32_t iterations, int32_t n_workgroups,
+                           uint64_t *ticks, void *stream);
 
 /* Text for the most recent failure on this thread ("" if none). */
 const char *rlhf_last_error_string(void);

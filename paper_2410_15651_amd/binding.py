@@ -33,7 +33,7 @@ EXPORTS = [
     "rlhf_token_logprobs_kl",
     "rlhf_token_logprobs_kl_rewards", "rlhf_sample_tokens", "rlhf_sample_tokens_workspace_bytes",
     "rlhf_sample_tokens_split", "rlhf_sample_tokens_topk", "rlhf_prefill_attention",
-    "rlhf_prefill_attention_wg", "rlhf_probe_stream_read",
+    "rlhf_prefill_attention_wg", "rlhf_probe_stream_read", "rlhf_probe_matrix_rate",
     "rlhf_last_error_string", "rlhf_version",
     "rlhf_alloc_sim_create", "rlhf_alloc_sim_destroy", "rlhf_alloc_sim_malloc", "rlhf_alloc_sim_free",
     "rlhf_alloc_sim_empty_cache", "rlhf_alloc_sim_stats",
@@ -135,6 +135,7 @@ def lib() -> ctypes.CDLL:
         L.rlhf_prefill_attention.argtypes = [P(AttnParams), vp, vp, i32, vp, vp, vp, vp, vp, vp]
         L.rlhf_prefill_attention_wg.argtypes = [P(AttnParams), vp, vp, i32, vp, vp, vp, vp, vp, i32, vp]
         L.rlhf_probe_stream_read.argtypes = [vp, sz, vp, vp]
+        L.rlhf_probe_matrix_rate.argtypes = [vp, sz, i32, i32, vp, vp]
         u64 = ctypes.c_uint64
         L.rlhf_alloc_sim_create.argtypes = [P(vp)]
         L.rlhf_alloc_sim_destroy.argtypes = [vp]
@@ -406,6 +407,13 @@ def rlhf_probe_stream_read(buffer, nbytes=None, sink=None, stream=None) -> None:
     if nbytes is None:
         nbytes = buffer.numel() * buffer.element_size()
     _check(lib().rlhf_probe_stream_read(_ptr(buffer), nbytes, _ptr(sink), _stream(stream)))
+
+
+def rlhf_probe_matrix_rate(operands, iterations, n_workgroups, ticks, nbytes=None, stream=None) -> None:
+    if nbytes is None:
+        nbytes = operands.numel() * operands.element_size()
+    _check(lib().rlhf_probe_matrix_rate(_ptr(operands), nbytes, iterations, n_workgroups, _ptr(ticks),
+                                        _stream(stream)))
 
 
 def rlhf_last_error_string() -> str:

@@ -247,6 +247,10 @@ def test_sampling_and_probe_entry_points_validate_before_launching():
     with pytest.raises(rb.RlhfError) as e:
         rb.rlhf_probe_stream_read(24, 64)
     assert e.value.status == rb.RLHF_ERR_INVALID
+    for args in ((0, 10, 1, 64), (24, 10, 1, 64), (16, -1, 1, 64), (16, 10, 0, 64), (16, 10, 1, 0), (16, 10, 1, 68)):
+        with pytest.raises(rb.RlhfError) as e:                               # operands, iterations, workgroups, ticks
+            rb.rlhf_probe_matrix_rate(args[0], args[1], args[2], args[3], nbytes=64)
+        assert e.value.status == rb.RLHF_ERR_INVALID, args
 
 
 @settings(max_examples=120, deadline=None)

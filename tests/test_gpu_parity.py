@@ -1373,6 +1373,26 @@ def test_read_probe_accepts_any_size(gu, nbytes):
         rb.rlhf_probe_stream_read(buf.data_ptr() + 8, 64)
 
 
+def test_matrix_probe_reports_a_duration_and_a_clock(gu):
+    """The probe's loop of matrix instructions runs to the end on any operand buffer (read modulo its length), and
+    its two counters give a shader clock inside what the device can hold."""
+    ticks = torch.zeros(3, dtype=torch.int64, device=gu.DEV)
+    for ops in (torch.zeros(8, dtype=torch.bfloat16, device=gu.DEV),            # 16 bytes: every lane reads them
+                torch.randn(4096 + 8, device=gu.DEV).to(torch.bfloat16)):       # not a multiple of a lane's share
+        rb.rlhf_probe_matrix_rate(ops, 2000, 8, ticks)
+        torch.cuda.synchronize()
+        wall, cycles, _ = ticks.cpu().tolist()
+        assert wall > 0 and 500 <= cycles / wall * 100 <= 3000, (wall, cycles)  # MHz
+    rb.rlhf_probe_matrix_rate(ops, 0, 1, ticks)                                 # no iterations: nothing to do
+    torch.cuda.synchronize()
+    with pytest.raises(rb.RlhfError):
+        rb.rlhf_probe_matrix_rate(ops.data_ptr() + 8, 10, 1, ticks, nbytes=64)
+    with pytest.raises(rb.RlhfError):
+        rb.rlhf_probe_matrix_rate(ops, 10, 0, ticks)
+    with pytest.raises(rb.RlhfError):
+        rb.rlhf_probe_matrix_rate(ops, 10, 1, 0)
+
+
 @pytest.mark.parametrize("cfg_index,batch", [(1, 4), (2, 5), (5, 3)])
 def test_rollout_demo_runs_the_whole_path(gu, cfg_index, batch):
     """The demo script composes every entry point in the order a rollout uses
