@@ -387,9 +387,13 @@ def test_attention_matches_oracle(gu, oracle, cfg_index, over):
         table, hl, _ = A.host_state()
         assert table.tolist() == A.model.page_table() and hl.tolist() == lens.tolist()
         expect = gu.oracle_attention(oracle, cfg, q, ks, vs, table, lens, A.n_pages)
-        out32 = gu.run_attention(cfg, A, q, out_dtype=rb.RLHF_F32).cpu().numpy().astype(np.float64)
+        dev32 = gu.run_attention(cfg, A, q, out_dtype=rb.RLHF_F32)
+        dev16 = gu.run_attention(cfg, A, q)
+        # the 16-bit output is the fp32 output rounded to nearest even, element for element
+        assert torch.equal(dev32.to(dev16.dtype).view(torch.int16), dev16.view(torch.int16))
+        out32 = dev32.cpu().numpy().astype(np.float64)
         err32 = np.abs(out32 - expect).max()
-        out16 = gu.run_attention(cfg, A, q).float().cpu().numpy().astype(np.float64)
+        out16 = dev16.float().cpu().numpy().astype(np.float64)
         err16 = np.abs(out16 - expect).max()
         _say(f"  max-abs err: f32 out {err32:.3e}, {cfg.kv_dtype} out {err16:.3e}")
         assert err32 <= ATTN_TOL

@@ -115,6 +115,8 @@ def test_prefill_matches_oracle(gu, oracle, cfg_index, over, how):
         _say(f"  max-abs err: f32 out {err32:.3e}, {cfg.kv_dtype} out {err16:.3e}")
         assert err32 <= ATTN_TOL
         assert err16 <= ATTN_TOL + ulp        # plus half an ulp of the 16-bit output itself
+        # the 16-bit output is the fp32 output rounded to nearest even, element for element
+        assert torch.equal(out32.to(out16.dtype).view(torch.int16), out16.view(torch.int16))
     finally:
         A.close()
 
