@@ -253,7 +253,10 @@ int rlhf_kv_arena_gather(const rlhf_kv_arena *arena, int32_t seq_id, int32_t sta
  * merge kernel's wavefront per query head is faster), while its stream is
  * being captured into a graph, on further streams, above 32768 (sequence, head)
  * units per call, and when the units are so few that one wavefront would have
- * to merge dozens of partials.  Both forms give bit-identical results; each is
+ * to merge dozens of partials (a call whose caches cannot exceed 8 MiB in all
+ * -- batch * heads * max_seq_len * head_dim * 4 bytes, so a tight max_seq_len
+ * helps -- is cut into fewer pieces instead, so that it still takes one launch:
+ * it is bound by latencies, not bytes).  Both forms give bit-identical results; each is
  * deterministic for given inputs, and neither depends on which physical pages
  * a sequence owns.  A stream destroyed while a call on it is still running
  * must not be replaced by a new stream that calls at once (the new one could
