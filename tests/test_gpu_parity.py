@@ -543,6 +543,8 @@ ONE_LAUNCH_SHAPES = [
     (2, dict(batch=8, len_lo=0, len_hi=700)),                                   # D=64
     (3, dict(batch=8, n_q_heads=40, n_kv_heads=40, len_lo=1, len_hi=300)),      # D=128
     (1, dict(batch=30, n_q_heads=12, n_kv_heads=12, len_lo=0, len_hi=500)),     # f16
+    (1, dict(batch=4, n_q_heads=12, n_kv_heads=12, len_lo=1, len_hi=512)),      # 48 units of at most 6 MB in all:
+                                                                                # cut into few ranges, one launch
     # grouped heads: always the split kernel and the merge kernel
     (5, dict(batch=32, n_q_heads=16, n_kv_heads=8, len_lo=0, len_hi=900)),      # groups of 2
     (5, dict(batch=24, n_q_heads=64, n_kv_heads=8, len_lo=100, len_hi=1300)),   # groups of 8
